@@ -1,0 +1,306 @@
+"""fp64 CPU oracle for the SPES MoE-layer hot path.  TEST INFRASTRUCTURE ONLY.
+
+This file is the yardstick the device kernels are compared against.  It is a
+plain, slow, definition-by-definition numpy implementation in float64; it shares
+no code with the device path and must never be imported by the product package.
+Only the tests, the smoke check and the benchmark's CPU-baseline leg use it.
+
+What it follows (paper sections; equation numbers count displayed equations in
+order of appearance):
+
+* MoE block  MoE(x) = sum_j G_j(x) E_j(x)                      -- Sec. 3.1, Eq. 2
+* softmax routing over all M experts, then top-k; drop-less     -- Sec. 3.2
+* SwiGLU experts  E(x) = W_d ( SiLU(W_g x) * W_u x )            -- Sec. 3.2
+* gate renormalisation over the chosen k (upcycled model)       -- Sec. 4 "Implementation details"
+* only assigned experts (and shared modules, i.e. the router)
+  receive parameter gradients; frozen experts still carry the
+  input gradient                                                -- Sec. 3.3, Eq. 3; App. A, block mask U_i
+* sparse synchronisation (average / direct assignment)          -- Sec. 3.3, Eq. 4; App. A sync rules
+* expert-merging warm-up (cosine similarity, top-K, task
+  arithmetic, all right-hand sides pre-merge)                   -- Sec. 3.3, Eq. 5-6; App. A merge step
+
+Every function takes numpy arrays of already-rounded inputs and up-converts them
+to float64; nothing is blocked, fused or reordered beyond "for each expert, the
+rows routed to it".  Pins for each function live in tests/test_oracle_*.py; no
+function here is "parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+F64 = np.float64
+
+
+def _f64(a):
+    return None if a is None else np.asarray(a, dtype=F64)
+
+
+# ----------------------------------------------------------------------------
+# routing: Sec. 3.2 (softmax routing, top-k, drop-less dispatch)
+# ----------------------------------------------------------------------------
+
+
+def router_logits(x, w_router, router_bias=None):
+    """s[t,e] = <x_t, w_router_e> (+ bias_e).  x [T,d], w_router [M,d]."""
+    s = _f64(x) @ _f64(w_router).T
+    if router_bias is not None:
+        s = s + _f64(router_bias)[None, :]
+    return s
+
+
+def softmax(s):
+    """Row softmax over all M experts, with the row maximum subtracted first."""
+    z = s - s.max(axis=1, keepdims=True)
+    e = np.exp(z)
+    return e / e.sum(axis=1, keepdims=True)
+
+
+def top_k(s, k):
+    """Indices of the k largest scores per row, in descending score order; ties go to the lower index."""
+    order = np.argsort(-s, axis=1, kind="stable")   # stable: equal scores keep ascending index order
+    return order[:, :k].astype(np.int32)
+
+
+def gates(p, idx, renorm):
+    """G_j(x) for the selected experts: the softmax probability, optionally renormalised over the k chosen."""
+    g = np.take_along_axis(p, idx.astype(np.int64), axis=1)
+    if renorm:
+        g = g / g.sum(axis=1, keepdims=True)
+    return g
+
+
+def routing_tables(idx, M):
+    """Drop-less dispatch tables for idx [T,k].
+
+    count[e]  = number of routed (token, slot) pairs with expert e
+    offset    = exclusive prefix sum of count, length M+1
+    perm[r]   = flat pair index t*k+j held by row r of the expert-contiguous order
+                (rows of one expert keep ascending flat index: a stable sort)
+    inv[t*k+j]= row of that pair
+    """
+    flat = idx.reshape(-1).astype(np.int64)
+    count = np.bincount(flat, minlength=M).astype(np.int32)
+    offset = np.zeros(M + 1, dtype=np.int32)
+    offset[1:] = np.cumsum(count)
+    perm = np.argsort(flat, kind="stable").astype(np.int32)
+    inv = np.empty_like(perm)
+    inv[perm] = np.arange(perm.size, dtype=np.int32)
+    return count, offset, perm, inv
+
+
+# ----------------------------------------------------------------------------
+# one SwiGLU expert on a block of rows: Sec. 3.2
+# ----------------------------------------------------------------------------
+
+
+def sigmoid(a):
+    return 1.0 / (1.0 + np.exp(-a))
+
+
+def expert_forward(x_rows, w_gate, w_up, w_down):
+    """a = W_g x, b = W_u x, h = SiLU(a)*b, yp = W_d h  for every row of x_rows [n,d].
+
+    w_gate, w_up are [f,d]; w_down is [d,f] (all stored [out,in]).
+    """
+    x_rows, w_gate, w_up, w_down = _f64(x_rows), _f64(w_gate), _f64(w_up), _f64(w_down)
+    a = x_rows @ w_gate.T
+    b = x_rows @ w_up.T
+    h = a * sigmoid(a) * b
+    yp = h @ w_down.T
+    return a, b, h, yp
+
+
+def expert_backward(x_rows, dyp_rows, a, b, h, w_gate, w_up, w_down):
+    """Gradients of one expert for upstream dyp_rows [n,d].
+
+    Returns dx_rows [n,d], dW_g [f,d], dW_u [f,d], dW_d [d,f].
+    """
+    x_rows, w_gate, w_up, w_down = _f64(x_rows), _f64(w_gate), _f64(w_up), _f64(w_down)
+    dh = dyp_rows @ w_down                       # yp = h W_d^T
+    sg = sigmoid(a)
+    da = dh * b * sg * (1.0 + a * (1.0 - sg))    # d/da [a*sigmoid(a)] = sg*(1 + a*(1-sg))
+    db = dh * a * sg
+    dx_rows = da @ w_gate + db @ w_up
+    d_w_down = dyp_rows.T @ h
+    d_w_gate = da.T @ x_rows
+    d_w_up = db.T @ x_rows
+    return dx_rows, d_w_gate, d_w_up, d_w_down
+
+
+# ----------------------------------------------------------------------------
+# the layer: Eq. 2 forward, chain rule backward with the block mask of Eq. 3
+# ----------------------------------------------------------------------------
+
+
+def moe_forward(x, w_router, router_bias, w_gate, w_up, w_down, k, renorm, keep=True):
+    """Forward of the routed feed-forward layer.
+
+    Returns a dict with y [T,d], logits, p, idx [T,k], gate [T,k], count, offset,
+    perm, inv, and (keep=True) per-pair intermediates a,b,h [T,k,f], yp [T,k,d]
+    indexed by (token, slot).
+    """
+    x = _f64(x)
+    T, d = x.shape
+    M = w_router.shape[0]
+    f = w_gate.shape[1]
+    s = router_logits(x, w_router, router_bias)
+    p = softmax(s)
+    idx = top_k(s, k)
+    g = gates(p, idx, renorm)
+    count, offset, perm, inv = routing_tables(idx, M)
+    a = np.zeros((T, k, f)); b = np.zeros((T, k, f)); h = np.zeros((T, k, f)); yp = np.zeros((T, k, d))
+    for e in range(M):
+        t_e, j_e = np.nonzero(idx == e)          # the pairs routed to expert e
+        if t_e.size == 0:
+            continue
+        a_e, b_e, h_e, yp_e = expert_forward(x[t_e], w_gate[e], w_up[e], w_down[e])
+        a[t_e, j_e], b[t_e, j_e], h[t_e, j_e], yp[t_e, j_e] = a_e, b_e, h_e, yp_e
+    y = np.zeros((T, d))
+    for j in range(k):                            # Eq. 2: weighted sum over the selected experts
+        y += g[:, j:j + 1] * yp[:, j, :]
+    out = dict(y=y, logits=s, p=p, idx=idx, gate=g, count=count, offset=offset, perm=perm, inv=inv)
+    if keep:
+        out.update(a=a, b=b, h=h, yp=yp)
+    return out
+
+
+def gating_backward(p, idx, gate, dgate, renorm):
+    """dL/dlogits [T,M] from dL/dgate [T,k], following the forward order:
+    softmax over all M -> pick k -> (optionally) divide by the sum of the picked."""
+    T, M = p.shape
+    dsel = dgate
+    if renorm:
+        S = np.take_along_axis(p, idx.astype(np.int64), axis=1).sum(axis=1, keepdims=True)
+        # gate_j = p_j / S  =>  dL/dp_j = (dgate_j - sum_i dgate_i gate_i) / S
+        dsel = (dgate - (dgate * gate).sum(axis=1, keepdims=True)) / S
+    dp = np.zeros((T, M))
+    np.put_along_axis(dp, idx.astype(np.int64), dsel, axis=1)
+    return p * (dp - (dp * p).sum(axis=1, keepdims=True))
+
+
+def moe_backward(fwd, dy, x, w_router, w_gate, w_up, w_down, renorm, wgrad_experts=None):
+    """Backward of the layer given the forward record `fwd` (keep=True) and dy [T,d].
+
+    The selected index set is treated as constant.  Input gradients flow through
+    every routed expert.  Weight gradients are returned per expert in dicts
+    d_w_gate/d_w_up/d_w_down keyed by expert id, for the experts in
+    `wgrad_experts` (default: all, so tests can compare any mask).
+    """
+    x, dy = _f64(x), _f64(dy)
+    T, d = x.shape
+    M = w_router.shape[0]
+    idx, g = fwd["idx"], fwd["gate"]
+    k = idx.shape[1]
+    if wgrad_experts is None:
+        wgrad_experts = range(M)
+    wgrad_experts = set(int(e) for e in wgrad_experts)
+    dgate = np.einsum("td,tjd->tj", dy, fwd["yp"])
+    dx = np.zeros((T, d))
+    dwg, dwu, dwd = {}, {}, {}
+    for e in range(M):
+        t_e, j_e = np.nonzero(idx == e)
+        if t_e.size == 0:
+            if e in wgrad_experts:
+                f = w_gate.shape[1]
+                dwg[e], dwu[e], dwd[e] = np.zeros((f, d)), np.zeros((f, d)), np.zeros((d, f))
+            continue
+        dyp_e = g[t_e, j_e][:, None] * dy[t_e]
+        dx_e, dwg_e, dwu_e, dwd_e = expert_backward(
+            x[t_e], dyp_e, fwd["a"][t_e, j_e], fwd["b"][t_e, j_e], fwd["h"][t_e, j_e],
+            w_gate[e], w_up[e], w_down[e])
+        np.add.at(dx, t_e, dx_e)
+        if e in wgrad_experts:
+            dwg[e], dwu[e], dwd[e] = dwg_e, dwu_e, dwd_e
+    dlogits = gating_backward(fwd["p"], idx, g, dgate, renorm)
+    d_w_router = dlogits.T @ x
+    dx_experts = dx.copy()
+    dx = dx + dlogits @ _f64(w_router)
+    return dict(dx=dx, dx_experts=dx_experts, d_w_router=d_w_router, dgate=dgate, dlogits=dlogits,
+                d_w_gate=dwg, d_w_up=dwu, d_w_down=dwd)
+
+
+def expert_weight_grads(e, fwd_routing, dy, x, w_gate_e, w_up_e, w_down_e):
+    """dW_g, dW_u, dW_d of the single expert e from routing results only (idx, gate).
+
+    Lets a large configuration be checked one expert at a time: it recomputes the
+    expert's forward on the rows routed to it and applies expert_backward.
+    """
+    idx, g = fwd_routing["idx"], fwd_routing["gate"]
+    t_e, j_e = np.nonzero(idx == e)
+    x_e = _f64(x)[t_e]
+    a, b, h, _ = expert_forward(x_e, w_gate_e, w_up_e, w_down_e)
+    dyp = g[t_e, j_e][:, None] * _f64(dy)[t_e]
+    _, dwg, dwu, dwd = expert_backward(x_e, dyp, a, b, h, w_gate_e, w_up_e, w_down_e)
+    return dwg, dwu, dwd
+
+
+# ----------------------------------------------------------------------------
+# synchronisation: Eq. 4 and its generalisation to several / no trainers
+# ----------------------------------------------------------------------------
+
+
+def sync_merge(base, stores, slot, node_weight=None):
+    """Global value of every expert after synchronisation.
+
+    base [M,E]: previous global values.  stores[i] [n_i,E]: node i's trained
+    experts; slot[i,j] = row of expert j in stores[i] or -1.  Expert j becomes the
+    node_weight-weighted mean of its trainers' copies (uniform weights and every
+    node training it: the FedAvg mean; a single trainer: direct assignment);
+    with no trainer it keeps its previous value.  Returns (dst [M,E], trainer_count [M]).
+    """
+    base = _f64(base)
+    M = base.shape[0]
+    n_nodes = len(stores)
+    w = np.ones(n_nodes) if node_weight is None else _f64(node_weight)
+    dst = base.copy()
+    trainer_count = np.zeros(M, dtype=np.int32)
+    for j in range(M):
+        num = np.zeros(base.shape[1])
+        den = 0.0
+        for i in range(n_nodes):                  # ascending node id
+            s = int(slot[i][j])
+            if s < 0:
+                continue
+            num += w[i] * _f64(stores[i][s])
+            den += w[i]
+            trainer_count[j] += 1
+        if trainer_count[j] > 0:
+            dst[j] = num / den
+    return dst, trainer_count
+
+
+# ----------------------------------------------------------------------------
+# expert-merging warm-up: Eq. 5 (similarity), top-K peers, Eq. 6 (task arithmetic)
+# ----------------------------------------------------------------------------
+
+
+def cosine_similarity(w_in):
+    """A[j,k] = <w_j, w_k> / (|w_j| |w_k|) over flattened input projections w_in [M,E]."""
+    w = _f64(w_in).reshape(w_in.shape[0], -1)
+    G = w @ w.T
+    n = np.sqrt(np.einsum("je,je->j", w, w))
+    return G / np.outer(n, n)
+
+
+def top_K_neighbours(A, K):
+    """Q_j: the K experts most similar to j, j itself excluded; ties go to the lower index."""
+    M = A.shape[0]
+    B = A.copy()
+    B[np.arange(M), np.arange(M)] = -np.inf
+    return np.argsort(-B, axis=1, kind="stable")[:, :K].astype(np.int32)
+
+
+def warmup_merge(phi, nbr, alpha):
+    """phi~_j = phi_j + (alpha/K) sum_{k in Q_j} (phi_k - phi_j), every phi on the right pre-merge.
+
+    phi [M,E] is one parameter matrix of all experts; call once per matrix with the same nbr.
+    """
+    phi = _f64(phi)
+    M, K = nbr.shape
+    out = np.empty_like(phi)
+    for j in range(M):
+        acc = np.zeros(phi.shape[1])
+        for kk in nbr[j]:
+            acc += phi[int(kk)] - phi[j]
+        out[j] = phi[j] + (alpha / K) * acc
+    return out
