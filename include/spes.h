@@ -1,0 +1,178 @@
+/*
+ * spes.h -- C ABI of the SPES MoE-layer hot path for AMD MI355X (gfx950).
+ *
+ * One node of SPES-style decentralised MoE pretraining stores every expert of a
+ * routed feed-forward layer but trains only its assigned subset (paper Sec. 3.3,
+ * "Expert Assignment and Local Training", Eq. 3).  This library is that node's
+ * training step through one such layer, plus the periodic synchronisation of
+ * node-local expert copies (Sec. 3.3 "Sparse Synchronization", Eq. 4) and the
+ * expert-merging warm-up (Sec. 3.3 "Expert-Merging Warm-Up", Eq. 5-6).
+ *
+ * Conventions that hold for every entry point
+ *  - Plain C linkage, plain pointers and sizes.  "DEVICE" pointers address GPU
+ *    memory of the current HIP device, "HOST" pointers ordinary host memory.
+ *  - The library allocates no device memory and keeps no state between calls.
+ *    Inputs, outputs, the context buffer and scratch are owned by the caller.
+ *  - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *    the default stream).  No entry point synchronises or copies device memory
+ *    back to the host; per-expert token counts are consumed on the device.
+ *  - HOST arrays are read before the call returns and may be freed afterwards.
+ *  - Return value: SPES_OK (0) or a negative spes_status.  Arguments are checked
+ *    before anything is launched, so a failed check has no side effects.
+ *  - Tensors are row-major with the innermost dimension contiguous.  Weight
+ *    matrices are stored [out_features, in_features].  DEVICE pointers must be
+ *    16-byte aligned.  Outputs must not alias inputs.
+ *  - dtype selects the storage type of parameters and activations (fp32, or
+ *    bf16 with round-to-nearest-even on every store); every accumulation is fp32.
+ *    Router logits, gates and all weight gradients are fp32 in both modes.
+ */
+#ifndef SPES_H_
+#define SPES_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPES_API __attribute__((visibility("default")))
+
+typedef enum {
+  SPES_OK = 0,
+  SPES_EINVAL = -1, /* null pointer, non-positive size, top_k > n_experts, bad dtype   */
+  SPES_ESHAPE = -2, /* a size this build does not support (see each call)              */
+  SPES_EALIGN = -3, /* a DEVICE pointer is not 16-byte aligned                         */
+  SPES_EHIP = -4    /* a kernel launch failed; see hipGetLastError                     */
+} spes_status;
+
+typedef enum { SPES_F32 = 0, SPES_BF16 = 1 } spes_dtype;
+
+/* Shape of one routed feed-forward layer (Sec. 3.1 Eq. 2; Sec. 3.2).
+ * Supported: 1 <= top_k <= n_experts <= 64; d_model and d_ff multiples of 8. */
+typedef struct {
+  int32_t T;           /* tokens in the batch                                         */
+  int32_t d_model;     /* d                                                           */
+  int32_t n_experts;   /* M                                                           */
+  int32_t d_ff;        /* f, hidden width of one SwiGLU expert                        */
+  int32_t top_k;       /* k experts per token                                         */
+  int32_t dtype;       /* spes_dtype                                                  */
+  int32_t renorm_topk; /* 1: gates are renormalised over the k chosen (Sec. 4,
+                          upcycled model); 0: gate = softmax probability over all M   */
+} spes_moe_shape;
+
+/* Byte offsets of the regions inside the context buffer; exposed so that tests
+ * can inspect routing tables and saved activations.  R = T*top_k routed rows. */
+typedef struct {
+  size_t total;
+  size_t logits;    /* [T,M] f32 router scores                                        */
+  size_t lse;       /* [T] f32 log-sum-exp of the scores                              */
+  size_t topk_idx;  /* [T,k] i32 copy of the selected experts                          */
+  size_t topk_gate; /* [T,k] f32 copy of their gates                                  */
+  size_t offset;    /* [M+1] i32 first row of each expert in expert-contiguous order  */
+  size_t perm;      /* [R] i32 row r holds routed pair perm[r] = t*k+j                */
+  size_t inv;       /* [R] i32 inverse of perm                                        */
+  size_t xp;        /* [R,d] permuted inputs                                          */
+  size_t a;         /* [R,f] gate projection  W_g x                                   */
+  size_t b;         /* [R,f] up projection    W_u x                                   */
+  size_t h;         /* [R,f] SiLU(a)*b                                                */
+  size_t yp;        /* [R,d] expert outputs before gating                             */
+  size_t dlogits;   /* [T,M] f32, written by the backward                             */
+  size_t dgate;     /* [T,k] f32, written by the backward                             */
+} spes_moe_ctx_layout;
+
+/* Size and layout of the context buffer that spes_moe_fwd fills and spes_moe_bwd
+ * consumes (it also holds the backward's scratch).  Returns 0 on a bad shape. */
+SPES_API size_t spes_moe_ctx_bytes(const spes_moe_shape* shape);
+SPES_API int spes_moe_ctx_describe(const spes_moe_shape* shape, spes_moe_ctx_layout* out);
+
+/* Forward of the routed SwiGLU layer: y_t = sum_j G_j(x_t) E_j(x_t) (Sec. 3.1 Eq. 2)
+ * with softmax routing over all M experts followed by top-k selection, drop-less
+ * dispatch (every selected pair is computed; Sec. 3.2) and SwiGLU experts
+ * E(x) = W_d (SiLU(W_g x) * W_u x).
+ *
+ *  x            DEVICE [T,d]      w_router DEVICE [M,d]
+ *  router_bias  DEVICE [M] f32 or NULL (added to the scores; receives no gradient)
+ *  w_gate,w_up  DEVICE [M,f,d]    w_down   DEVICE [M,d,f]
+ *  y            DEVICE [T,d] out
+ *  topk_idx     DEVICE [T,k] i32 out: selected experts in descending score order,
+ *               equal scores resolved to the lower expert id
+ *  topk_gate    DEVICE [T,k] f32 out
+ *  expert_count DEVICE [M] i32 out: routed pairs per expert (sums to T*k)
+ *  ctx          DEVICE, spes_moe_ctx_bytes(shape) bytes, 256-byte aligned
+ */
+SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void* w_router,
+                          const float* router_bias, const void* w_gate, const void* w_up,
+                          const void* w_down, void* y, int32_t* topk_idx, float* topk_gate,
+                          int32_t* expert_count, void* ctx, void* stream);
+
+/* Backward of the same layer for upstream gradient dy.  The selected expert set
+ * is treated as constant.  The input gradient flows through every routed expert,
+ * trainable or frozen; weight gradients are produced only for experts whose mask
+ * byte is non-zero (Sec. 3.3 Eq. 3; App. A, block mask U_i), into compact
+ * buffers with one slot per trainable expert in ascending expert id, so frozen
+ * experts own no gradient memory.  The router belongs to the shared modules that
+ * every node trains, so d_w_router is always produced.
+ *
+ *  dy, x          DEVICE [T,d]; weights as in the forward, ctx as left by it
+ *  trainable_mask HOST  [M] bytes
+ *  dx             DEVICE [T,d] out
+ *  d_w_router     DEVICE [M,d] f32
+ *  d_w_gate,d_w_up DEVICE [n_trainable,f,d] f32;  d_w_down DEVICE [n_trainable,d,f] f32
+ *                 (may be NULL when no expert is trainable)
+ *  accumulate     0: weight gradients are overwritten; 1: added to (micro-batches)
+ */
+SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const void* x,
+                          const void* w_router, const void* w_gate, const void* w_up,
+                          const void* w_down, void* ctx, const uint8_t* trainable_mask, void* dx,
+                          float* d_w_router, float* d_w_gate, float* d_w_up, float* d_w_down,
+                          int32_t accumulate, void* stream);
+
+/* Synchronisation of node-local expert copies (Sec. 3.3 Eq. 4; App. A sync rules),
+ * for one parameter matrix of every expert.  Expert j becomes the weighted mean
+ * of the copies held by the nodes that trained it,
+ *      dst[j] = sum_i w_i * store_i[slot[i][j]] / sum_i w_i   over i with slot[i][j] >= 0,
+ * which is FedAvg when all nodes train it with equal weights and a direct
+ * (bit-exact) assignment when a single node does.  An expert nobody trained keeps
+ * the value already in dst.
+ *
+ *  n_experts >= 1; elems = elements of the matrix per expert, a multiple of 8
+ *  node_store   HOST  [n_nodes] DEVICE pointers; store i is [n_i, elems]
+ *  slot         HOST  [n_nodes, n_experts] i32: row of expert j in store i, or -1
+ *  node_weight  HOST  [n_nodes] f32 (> 0) or NULL for equal weights
+ *  dst          DEVICE [n_experts, elems] in/out
+ *  trainer_count DEVICE [n_experts] i32 out or NULL: number of trainers per expert
+ *  At most 224 trainers per expert (SPES_ESHAPE beyond).
+ */
+SPES_API int spes_expert_merge(int32_t n_experts, int64_t elems, int32_t dtype, int32_t n_nodes,
+                               const void* const* node_store, const int32_t* slot,
+                               const float* node_weight, void* dst, int32_t* trainer_count,
+                               void* stream);
+
+/* Expert-merging warm-up (Sec. 3.3 Eq. 5-6; App. A merge step).  Cosine similarity
+ * A[j][k] between the flattened input projections w_in[j], w_in[k]; Q_j = the top_K
+ * most similar experts to j, j excluded, equal similarities resolved to the lower
+ * id; then for each of the n_mats parameter matrices
+ *      dst[m][j] = src[m][j] + (alpha/top_K) * sum_{k in Q_j} (src[m][k] - src[m][j]),
+ * every right-hand side being the pre-merge value (out of place: dst[m] != src[m]).
+ *
+ *  1 <= top_K < n_experts <= 64
+ *  w_in     DEVICE [M, elems_in], elems_in a multiple of 8
+ *  src,dst  HOST arrays of n_mats DEVICE pointers, matrix m is [M, elems[m]]
+ *  elems    HOST  [n_mats], each a multiple of 8
+ *  sim      DEVICE [M,M] f32 out or NULL;  nbr DEVICE [M,top_K] i32 out
+ *  scratch  DEVICE, spes_warmup_scratch_bytes(M, elems_in) bytes
+ */
+SPES_API size_t spes_warmup_scratch_bytes(int32_t n_experts, int64_t elems_in);
+SPES_API int spes_expert_warmup_merge(int32_t n_experts, int32_t dtype, int32_t top_K, float alpha,
+                                      const void* w_in, int64_t elems_in, int32_t n_mats,
+                                      const void* const* src, void* const* dst,
+                                      const int64_t* elems, float* sim, int32_t* nbr,
+                                      void* scratch, void* stream);
+
+SPES_API const char* spes_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPES_H_ */

@@ -1,0 +1,321 @@
+// C ABI of the library: argument checks, context layout and the launch
+// sequences of the forward, backward, synchronisation and warm-up merge.
+#include <cstring>
+
+#include "kernels.h"
+
+using namespace spes;
+
+namespace {
+
+struct Layout {
+  spes_moe_ctx_layout pub;
+  size_t block_counts, tab_simt, tab_mfma, dyp, da, db, dxp;
+  int max_tiles;
+};
+
+bool shape_ok(const spes_moe_shape* s) {
+  if (s == nullptr) return false;
+  if (s->T <= 0 || s->d_model <= 0 || s->n_experts <= 0 || s->d_ff <= 0 || s->top_k <= 0) return false;
+  if (s->top_k > s->n_experts) return false;
+  if (s->dtype != SPES_F32 && s->dtype != SPES_BF16) return false;
+  return true;
+}
+
+int shape_supported(const spes_moe_shape* s) {
+  if (!shape_ok(s)) return SPES_EINVAL;
+  if (s->n_experts > kMaxExperts) return SPES_ESHAPE;
+  if (s->d_model % 8 || s->d_ff % 8) return SPES_ESHAPE;
+  const long R = (long)s->T * s->top_k;
+  if (R > (1L << 22) - 4096) return SPES_ESHAPE;   // row-tile tables index a 16-bit grid dimension
+  return SPES_OK;
+}
+
+Layout make_layout(const spes_moe_shape* s) {
+  Layout L;
+  const size_t T = s->T, d = s->d_model, M = s->n_experts, f = s->d_ff, k = s->top_k;
+  const size_t R = T * k, es = s->dtype == SPES_F32 ? 4 : 2;
+  L.max_tiles = (int)(R / 64 + M + 1);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += round_up(bytes, 256); return o; };
+  L.pub.logits = take(T * M * 4);
+  L.pub.lse = take(T * 4);
+  L.pub.topk_idx = take(R * 4);
+  L.pub.topk_gate = take(R * 4);
+  L.pub.offset = take((M + 1) * 4);
+  L.pub.perm = take(R * 4);
+  L.pub.inv = take(R * 4);
+  L.block_counts = take((size_t)routing_blocks((int)R) * kMaxExperts * 4);
+  L.tab_simt = take((1 + 2 * (size_t)L.max_tiles) * 4);
+  L.tab_mfma = take((1 + 2 * (size_t)L.max_tiles) * 4);
+  L.pub.xp = take(R * d * es);
+  L.pub.a = take(R * f * es);
+  L.pub.b = take(R * f * es);
+  L.pub.h = take(R * f * es);
+  L.pub.yp = take(R * d * es);
+  L.pub.dlogits = take(T * M * 4);
+  L.pub.dgate = take(T * k * 4);
+  L.dyp = take(R * d * es);
+  L.da = take(R * f * es);
+  L.db = take(R * f * es);
+  L.dxp = take(R * d * es);
+  L.pub.total = off;
+  return L;
+}
+
+template <typename T>
+T* at(void* base, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(base) + off); }
+
+void ragged_tables(GemmArgs& g, void* ctx, const Layout& L) {
+  int* tab = at<int>(ctx, L.tab_simt);
+  g.n_tiles = tab;
+  g.tile_expert = tab + 1;
+  g.tile_row0 = tab + 1 + L.max_tiles;
+  g.offset = at<int>(ctx, L.pub.offset);
+  g.max_tiles = L.max_tiles;
+}
+
+GemmArgs blank() {
+  GemmArgs g;
+  memset(&g, 0, sizeof(g));
+  g.npairs = 1;
+  g.n_groups = 1;
+  return g;
+}
+
+#define SPES_TRY(expr) do { int rc_ = (expr); if (rc_ != SPES_OK) return rc_; } while (0)
+
+}  // namespace
+
+extern "C" {
+
+SPES_API size_t spes_moe_ctx_bytes(const spes_moe_shape* shape) {
+  if (shape_supported(shape) != SPES_OK) return 0;
+  return make_layout(shape).pub.total;
+}
+
+SPES_API int spes_moe_ctx_describe(const spes_moe_shape* shape, spes_moe_ctx_layout* out) {
+  if (out == nullptr) return SPES_EINVAL;
+  SPES_TRY(shape_supported(shape));
+  *out = make_layout(shape).pub;
+  return SPES_OK;
+}
+
+SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void* w_router, const float* router_bias,
+                          const void* w_gate, const void* w_up, const void* w_down, void* y, int32_t* topk_idx,
+                          float* topk_gate, int32_t* expert_count, void* ctx, void* stream) {
+  SPES_TRY(shape_supported(shape));
+  if (!x || !w_router || !w_gate || !w_up || !w_down || !y || !topk_idx || !topk_gate || !expert_count || !ctx)
+    return SPES_EINVAL;
+  if (!aligned16(x) || !aligned16(w_router) || !aligned16(w_gate) || !aligned16(w_up) || !aligned16(w_down) || !aligned16(y) ||
+      !aligned16(topk_idx) || !aligned16(topk_gate) || !aligned16(expert_count) || !aligned16(ctx) ||
+      (router_bias && !aligned16(router_bias)))
+    return SPES_EALIGN;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const Layout L = make_layout(shape);
+  const int T = shape->T, d = shape->d_model, M = shape->n_experts, f = shape->d_ff, k = shape->top_k, dt = shape->dtype;
+  const long R = (long)T * k;
+
+  // router scores: logits[T,M] = x W_r^T
+  {
+    GemmArgs g = blank();
+    g.A[0] = x; g.a_ms = d; g.a_ks = 1;
+    g.B[0] = w_router; g.b_ns = d; g.b_ks = 1;
+    g.Kdim = d; g.kchunk = d; g.Mdim = T; g.Ndim = M;
+    g.C[0] = at<float>(ctx, L.pub.logits); g.c_ms = M; g.c_f32 = 1;
+    SPES_TRY(launch_gemm_simt(dt, dt, kGroupedK, kEpiStore, g, s));
+  }
+  SPES_TRY(launch_topk_gate(at<float>(ctx, L.pub.logits), router_bias, T, M, k, shape->renorm_topk, topk_idx, topk_gate,
+                            at<int>(ctx, L.pub.topk_idx), at<float>(ctx, L.pub.topk_gate), at<float>(ctx, L.pub.lse), s));
+  SPES_TRY(launch_routing_tables(topk_idx, (int)R, M, at<int>(ctx, L.block_counts), expert_count, at<int>(ctx, L.pub.offset),
+                                 at<int>(ctx, L.pub.perm), at<int>(ctx, L.pub.inv), simt_row_tile(), at<int>(ctx, L.tab_simt), 0,
+                                 at<int>(ctx, L.tab_mfma), L.max_tiles, s));
+  SPES_TRY(launch_permute(dt, x, at<int>(ctx, L.pub.perm), k, at<void>(ctx, L.pub.xp), R, d, s));
+  // a = xp W_g^T, b = xp W_u^T, h = SiLU(a) * b
+  {
+    GemmArgs g = blank();
+    g.A[0] = at<void>(ctx, L.pub.xp); g.a_ms = d; g.a_ks = 1;
+    g.B[0] = w_gate; g.B[1] = w_up; g.b_ns = d; g.b_ks = 1; g.b_gs = (long)f * d;
+    g.Kdim = d; g.Ndim = f;
+    g.C[0] = at<void>(ctx, L.pub.a); g.C[1] = at<void>(ctx, L.pub.b); g.C[2] = at<void>(ctx, L.pub.h); g.c_ms = f;
+    ragged_tables(g, ctx, L);
+    SPES_TRY(launch_gemm_simt(dt, dt, kRaggedM, kEpiSwiglu, g, s));
+  }
+  // yp = h W_d^T
+  {
+    GemmArgs g = blank();
+    g.A[0] = at<void>(ctx, L.pub.h); g.a_ms = f; g.a_ks = 1;
+    g.B[0] = w_down; g.b_ns = f; g.b_ks = 1; g.b_gs = (long)d * f;
+    g.Kdim = f; g.Ndim = d;
+    g.C[0] = at<void>(ctx, L.pub.yp); g.c_ms = d;
+    ragged_tables(g, ctx, L);
+    SPES_TRY(launch_gemm_simt(dt, dt, kRaggedM, kEpiStore, g, s));
+  }
+  SPES_TRY(launch_combine(dt, at<void>(ctx, L.pub.yp), at<int>(ctx, L.pub.inv), topk_gate, y, T, d, k, s));
+  return SPES_OK;
+}
+
+SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const void* x, const void* w_router,
+                          const void* w_gate, const void* w_up, const void* w_down, void* ctx,
+                          const uint8_t* trainable_mask, void* dx, float* d_w_router, float* d_w_gate, float* d_w_up,
+                          float* d_w_down, int32_t accumulate, void* stream) {
+  SPES_TRY(shape_supported(shape));
+  if (!dy || !x || !w_router || !w_gate || !w_up || !w_down || !ctx || !trainable_mask || !dx || !d_w_router) return SPES_EINVAL;
+  const int T = shape->T, d = shape->d_model, M = shape->n_experts, f = shape->d_ff, k = shape->top_k, dt = shape->dtype;
+  int n_train = 0;
+  unsigned char train_list[kMaxExperts];
+  for (int e = 0; e < M; ++e)
+    if (trainable_mask[e]) train_list[n_train++] = (unsigned char)e;
+  if (n_train > 0 && (!d_w_gate || !d_w_up || !d_w_down)) return SPES_EINVAL;
+  if (!aligned16(dy) || !aligned16(x) || !aligned16(w_router) || !aligned16(w_gate) || !aligned16(w_up) || !aligned16(w_down) ||
+      !aligned16(ctx) || !aligned16(dx) || !aligned16(d_w_router) || !aligned16(d_w_gate) || !aligned16(d_w_up) ||
+      !aligned16(d_w_down))
+    return SPES_EALIGN;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const Layout L = make_layout(shape);
+  const int* inv = at<int>(ctx, L.pub.inv);
+  const float* gate = at<float>(ctx, L.pub.topk_gate);   // the forward's own copies: its outputs belong to the caller
+  const int* idx = at<int>(ctx, L.pub.topk_idx);
+
+  // dyp = gate * dy (expert-contiguous), dgate = <dy, yp>
+  SPES_TRY(launch_dy_scatter(dt, dy, at<void>(ctx, L.pub.yp), inv, gate, at<void>(ctx, L.dyp), at<float>(ctx, L.pub.dgate), T, d,
+                             k, s));
+  SPES_TRY(launch_gating_bwd(at<float>(ctx, L.pub.logits), at<float>(ctx, L.pub.lse), idx, gate, at<float>(ctx, L.pub.dgate), T,
+                             M, k, shape->renorm_topk, at<float>(ctx, L.pub.dlogits), s));
+  // dh = dyp W_d, then da, db through the SwiGLU
+  {
+    GemmArgs g = blank();
+    g.A[0] = at<void>(ctx, L.dyp); g.a_ms = d; g.a_ks = 1;
+    g.B[0] = w_down; g.b_ns = 1; g.b_ks = f; g.b_gs = (long)d * f;
+    g.Kdim = d; g.Ndim = f;
+    g.E[0] = at<void>(ctx, L.pub.a); g.E[1] = at<void>(ctx, L.pub.b);
+    g.C[0] = at<void>(ctx, L.da); g.C[1] = at<void>(ctx, L.db); g.c_ms = f;
+    ragged_tables(g, ctx, L);
+    SPES_TRY(launch_gemm_simt(dt, dt, kRaggedM, kEpiDSwiglu, g, s));
+  }
+  // dxp = da W_g + db W_u
+  {
+    GemmArgs g = blank();
+    g.npairs = 2;
+    g.A[0] = at<void>(ctx, L.da); g.A[1] = at<void>(ctx, L.db); g.a_ms = f; g.a_ks = 1;
+    g.B[0] = w_gate; g.B[1] = w_up; g.b_ns = 1; g.b_ks = d; g.b_gs = (long)f * d;
+    g.Kdim = f; g.Ndim = d;
+    g.C[0] = at<void>(ctx, L.dxp); g.c_ms = d;
+    ragged_tables(g, ctx, L);
+    SPES_TRY(launch_gemm_simt(dt, dt, kRaggedM, kEpiStore, g, s));
+  }
+  // weight gradients of the trainable experts only, into their compact slots
+  if (n_train > 0) {
+    GemmArgs g = blank();
+    g.n_groups = n_train;
+    memcpy(g.group_expert, train_list, n_train);
+    g.offset = at<int>(ctx, L.pub.offset);
+    g.c_f32 = 1; g.accumulate = accumulate;
+    // dW_d[d,f] = dyp^T h
+    g.A[0] = at<void>(ctx, L.dyp); g.a_ms = 1; g.a_ks = d;
+    g.B[0] = at<void>(ctx, L.pub.h); g.b_ns = 1; g.b_ks = f;
+    g.Mdim = d; g.Ndim = f; g.C[0] = d_w_down; g.c_ms = f; g.c_gs = (long)d * f;
+    SPES_TRY(launch_gemm_simt(dt, dt, kGroupedK, kEpiStore, g, s));
+    // dW_g[f,d] = da^T xp ; dW_u[f,d] = db^T xp
+    g.B[0] = at<void>(ctx, L.pub.xp); g.b_ns = 1; g.b_ks = d;
+    g.a_ms = 1; g.a_ks = f; g.Mdim = f; g.Ndim = d; g.c_ms = d; g.c_gs = (long)f * d;
+    g.A[0] = at<void>(ctx, L.da); g.C[0] = d_w_gate;
+    SPES_TRY(launch_gemm_simt(dt, dt, kGroupedK, kEpiStore, g, s));
+    g.A[0] = at<void>(ctx, L.db); g.C[0] = d_w_up;
+    SPES_TRY(launch_gemm_simt(dt, dt, kGroupedK, kEpiStore, g, s));
+  }
+  // dW_r[M,d] = dlogits^T x
+  {
+    GemmArgs g = blank();
+    g.A[0] = at<float>(ctx, L.pub.dlogits); g.a_ms = 1; g.a_ks = M;
+    g.B[0] = x; g.b_ns = 1; g.b_ks = d;
+    g.Kdim = T; g.kchunk = T; g.Mdim = M; g.Ndim = d;
+    g.C[0] = d_w_router; g.c_ms = d; g.c_f32 = 1; g.accumulate = accumulate;
+    SPES_TRY(launch_gemm_simt(SPES_F32, dt, kGroupedK, kEpiStore, g, s));
+  }
+  // dx = unpermuted sum of dxp + dlogits W_r
+  SPES_TRY(launch_dx_gather(dt, at<void>(ctx, L.dxp), inv, at<float>(ctx, L.pub.dlogits), w_router, dx, T, d, k, M, s));
+  return SPES_OK;
+}
+
+SPES_API int spes_expert_merge(int32_t n_experts, int64_t elems, int32_t dtype, int32_t n_nodes,
+                               const void* const* node_store, const int32_t* slot, const float* node_weight, void* dst,
+                               int32_t* trainer_count, void* stream) {
+  if (n_experts <= 0 || elems <= 0 || n_nodes <= 0 || !node_store || !slot || !dst) return SPES_EINVAL;
+  if (dtype != SPES_F32 && dtype != SPES_BF16) return SPES_EINVAL;
+  if (elems % 8) return SPES_ESHAPE;
+  if (!aligned16(dst) || (trainer_count && !aligned16(trainer_count))) return SPES_EALIGN;
+  for (int i = 0; i < n_nodes; ++i) {
+    bool used = false;
+    for (int j = 0; j < n_experts; ++j) used |= slot[(long)i * n_experts + j] >= 0;
+    if (used && !node_store[i]) return SPES_EINVAL;
+    if (used && !aligned16(node_store[i])) return SPES_EALIGN;
+    if (node_weight && !(node_weight[i] > 0.f)) return SPES_EINVAL;
+  }
+  for (int j = 0; j < n_experts; ++j) {
+    int n = 0;
+    for (int i = 0; i < n_nodes; ++i) n += slot[(long)i * n_experts + j] >= 0;
+    if (n > 224) return SPES_ESHAPE;
+  }
+  return launch_sync_merge(dtype, n_experts, elems, n_nodes, node_store, slot, node_weight, dst, trainer_count,
+                           static_cast<hipStream_t>(stream));
+}
+
+static int gram_groups(int64_t elems_in) {
+  long g = (elems_in + 4095) / 4096;
+  if (g > 1024) g = 1024;
+  if (g < 1) g = 1;
+  return (int)g;
+}
+
+SPES_API size_t spes_warmup_scratch_bytes(int32_t n_experts, int64_t elems_in) {
+  if (n_experts <= 0 || n_experts > kMaxExperts || elems_in <= 0) return 0;
+  return (size_t)gram_groups(elems_in) * n_experts * n_experts * 4;
+}
+
+SPES_API int spes_expert_warmup_merge(int32_t n_experts, int32_t dtype, int32_t top_K, float alpha, const void* w_in,
+                                      int64_t elems_in, int32_t n_mats, const void* const* src, void* const* dst,
+                                      const int64_t* elems, float* sim, int32_t* nbr, void* scratch, void* stream) {
+  if (n_experts <= 1 || top_K <= 0 || top_K >= n_experts || !w_in || elems_in <= 0 || n_mats < 0 || !nbr || !scratch)
+    return SPES_EINVAL;
+  if (dtype != SPES_F32 && dtype != SPES_BF16) return SPES_EINVAL;
+  if (n_mats > 0 && (!src || !dst || !elems)) return SPES_EINVAL;
+  if (n_experts > kMaxExperts || elems_in % 8 || elems_in >= (1LL << 31)) return SPES_ESHAPE;
+  if (!aligned16(w_in) || !aligned16(nbr) || !aligned16(scratch) || (sim && !aligned16(sim))) return SPES_EALIGN;
+  for (int m = 0; m < n_mats; ++m) {
+    if (!src[m] || !dst[m] || src[m] == dst[m] || elems[m] <= 0) return SPES_EINVAL;
+    if (elems[m] % 8) return SPES_ESHAPE;
+    if (!aligned16(src[m]) || !aligned16(dst[m])) return SPES_EALIGN;
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int M = n_experts;
+  const int ng = gram_groups(elems_in);
+  const long kchunk = (elems_in + ng - 1) / ng;
+  {
+    // Gram matrix of the flattened input projections, split along the long contraction
+    GemmArgs g = blank();
+    g.A[0] = w_in; g.a_ms = elems_in; g.a_ks = 1;
+    g.B[0] = w_in; g.b_ns = elems_in; g.b_ks = 1;
+    g.Kdim = (int)elems_in; g.kchunk = (int)kchunk; g.n_groups = ng;
+    g.Mdim = M; g.Ndim = M;
+    g.C[0] = scratch; g.c_ms = M; g.c_gs = (long)M * M; g.c_f32 = 1;
+    SPES_TRY(launch_gemm_simt(dtype, dtype, kGroupedK, kEpiStore, g, s));
+  }
+  SPES_TRY(launch_sim_topk(static_cast<const float*>(scratch), ng, M, top_K, sim, nbr, s));
+  for (int m = 0; m < n_mats; ++m)
+    SPES_TRY(launch_warmup_mix(dtype, M, elems[m], top_K, alpha, src[m], dst[m], nbr, s));
+  return SPES_OK;
+}
+
+SPES_API const char* spes_strerror(int code) {
+  switch (code) {
+    case SPES_OK: return "ok";
+    case SPES_EINVAL: return "invalid argument (null pointer, non-positive size, top_k > n_experts or unknown dtype)";
+    case SPES_ESHAPE: return "unsupported shape (n_experts > 64, a feature size not a multiple of 8, or too many rows/trainers)";
+    case SPES_EALIGN: return "device pointer not 16-byte aligned";
+    case SPES_EHIP: return "HIP kernel launch failed";
+    default: return "unknown error";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,55 @@
+// Problem description shared by the grouped GEMM kernels.
+//
+// Every contraction of the layer is written as  C(m,n) = sum_k A(m,k) * B(n,k)
+// with element strides for each operand, in one of two groupings:
+//
+//  kRaggedM  (forward and input-gradient GEMMs): the rows m are the routed rows
+//            in expert-contiguous order; a device-side tile table maps each row
+//            tile to its expert, whose weight matrix is operand B.
+//  kGroupedK (weight gradients, router GEMMs, Gram matrix): each group
+//            contracts over its own range of k -- the routed rows of one
+//            trainable expert, or a uniform chunk of a long contraction.
+#pragma once
+#include "common.h"
+
+namespace spes {
+
+enum GemmMode { kRaggedM = 0, kGroupedK = 1 };
+enum GemmEpi {
+  kEpiStore = 0,    // C[0] = acc (or += when accumulate)
+  kEpiSwiglu = 1,   // two accumulators a (pair 0), b (pair 1): C[0]=a, C[1]=b, C[2]=SiLU(a)*b
+  kEpiDSwiglu = 2   // acc = dh; with saved a=E[0], b=E[1]: C[0]=da, C[1]=db
+};
+
+struct GemmArgs {
+  const void* A[2];
+  const void* B[2];
+  long a_ms, a_ks;        // element strides of A along m, k
+  long b_ns, b_ks, b_gs;  // element strides of B along n, k, and per expert (kRaggedM)
+  int npairs;             // kEpiStore/kEpiDSwiglu: (A,B) pairs accumulated into one result
+  int Kdim;               // contraction length of each pair (kRaggedM) / total K (kGroupedK, uniform chunks)
+  void* C[3];
+  const void* E[2];
+  long c_ms;              // row stride of C and E (n stride is 1)
+  long c_gs;              // per-group stride of C (kGroupedK)
+  int c_f32;              // C is float whatever the storage type
+  int accumulate;
+  int Mdim, Ndim;         // extent of m (kGroupedK) and of n
+  // kRaggedM
+  const int* tile_expert;
+  const int* tile_row0;
+  const int* n_tiles;
+  const int* offset;      // [M+1] first routed row of each expert
+  int max_tiles;
+  // kGroupedK
+  int n_groups;
+  int kchunk;             // offset == nullptr: group g contracts k in [g*kchunk, min(Kdim,(g+1)*kchunk))
+  unsigned char group_expert[64];  // offset != nullptr: group g contracts rows [offset[e], offset[e+1]), e = group_expert[g]
+};
+
+__device__ __forceinline__ float sigmoidf_(float a) { return 1.0f / (1.0f + __expf(-a)); }
+
+// launchers (storage type T of A/B/C unless stated); defined in gemm_simt.hip / gemm_mfma.hip
+int launch_gemm_simt(int dtype_a, int dtype_b, int mode, int epi, const GemmArgs& g, hipStream_t s);
+
+}  // namespace spes

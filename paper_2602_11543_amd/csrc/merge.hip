@@ -1,0 +1,207 @@
+// Streaming kernels of the synchronisation step: the weighted average of
+// node-local expert copies (paper Sec. 3.3 Eq. 4), and the expert-merging
+// warm-up (Eq. 5-6): similarity -> top-K peers -> task-arithmetic mix.
+// Pure HBM streams: 16-byte vectors, fp32 arithmetic, one rounding on store.
+#include <vector>
+
+#include "kernels.h"
+
+namespace spes {
+namespace {
+
+constexpr int kMergeEntries = 224;   // (source pointer, weight) pairs per launch
+constexpr int kMergeExperts = 32;    // experts per launch
+
+struct MergeTable {
+  const void* src[kMergeEntries];
+  float w[kMergeEntries];            // weight / sum of weights over the expert's trainers
+  long dst_off[kMergeExperts];       // element offset of the expert in dst
+  int first[kMergeExperts + 1];      // entries [first[e], first[e+1]) belong to expert e of this launch
+};
+
+// dst = c_0 + sum_{i>0} w_i (c_i - c_0): equal to the weighted mean because the
+// weights sum to one; exact when all copies agree and a plain copy for one trainer.
+template <typename T>
+__global__ __launch_bounds__(256) void sync_merge_kernel(const MergeTable tb, T* __restrict__ dst, long nvec) {
+  constexpr int N = Vec16<T>::N;
+  const int e = blockIdx.y;
+  const int b = tb.first[e], n = tb.first[e + 1] - b;
+  T* out = dst + tb.dst_off[e];
+  const long stride = (long)gridDim.x * 256;
+  for (long v = (long)blockIdx.x * 256 + threadIdx.x; v < nvec; v += stride) {
+    Vec16<T> q;
+    q.load(reinterpret_cast<const T*>(tb.src[b]) + v * N);
+    if (n > 1) {
+      float f0[N], acc[N];
+      q.unpack(f0);
+#pragma unroll
+      for (int i = 0; i < N; ++i) acc[i] = f0[i];
+      for (int s = 1; s < n; ++s) {
+        Vec16<T> qs;
+        qs.load(reinterpret_cast<const T*>(tb.src[b + s]) + v * N);
+        float f[N];
+        qs.unpack(f);
+        const float w = tb.w[b + s];
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] = fmaf(w, f[i] - f0[i], acc[i]);
+      }
+      q.pack(acc);
+    }
+    q.store(out + v * N);
+  }
+}
+
+struct CountTable {
+  int base, n;
+  unsigned char c[1024];
+};
+__global__ void write_counts_kernel(const CountTable tb, int* __restrict__ trainer_count) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < tb.n) trainer_count[tb.base + i] = tb.c[i];
+}
+
+// Sum the Gram partials in a fixed order, normalise to cosines, pick each row's top-K peers.
+__global__ __launch_bounds__(256) void sim_topk_kernel(const float* __restrict__ partial, int n_partial, int M, int K,
+                                                       float* __restrict__ sim, int* __restrict__ nbr) {
+  __shared__ float G[kMaxExperts][kMaxExperts + 1];
+  const int tid = threadIdx.x;
+  for (int i = tid; i < M * M; i += 256) {
+    float acc = 0.f;
+    for (int p = 0; p < n_partial; ++p) acc += partial[(long)p * M * M + i];
+    G[i / M][i % M] = acc;
+  }
+  __syncthreads();
+  const int lane = tid & 63, w = tid >> 6;
+  for (int j = w; j < M; j += 4) {
+    float a = -INFINITY;
+    if (lane < M) {
+      a = G[j][lane] / sqrtf(G[j][j] * G[lane][lane]);
+      if (sim != nullptr) sim[j * M + lane] = a;
+      if (lane == j) a = -INFINITY;
+    }
+    bool taken = false;
+    int mine = 0;
+    for (int i = 0; i < K; ++i) {
+      float v = taken ? -INFINITY : a;
+      int ix = lane;
+      wave_argmax(v, ix);
+      if (lane == ix) taken = true;
+      if (lane == i) mine = ix;
+    }
+    if (lane < K) nbr[j * K + lane] = mine;
+  }
+}
+
+// dst[j] = src[j] + scale * sum_{q in nbr[j]} (src[q] - src[j])
+template <typename T>
+__global__ __launch_bounds__(256) void warmup_mix_kernel(const T* __restrict__ src, T* __restrict__ dst,
+                                                         const int* __restrict__ nbr, int K, float scale, long nvec, long elems) {
+  constexpr int N = Vec16<T>::N;
+  const int j = blockIdx.y;
+  const long stride = (long)gridDim.x * 256;
+  for (long v = (long)blockIdx.x * 256 + threadIdx.x; v < nvec; v += stride) {
+    Vec16<T> q;
+    q.load(src + (long)j * elems + v * N);
+    float f0[N], acc[N];
+    q.unpack(f0);
+#pragma unroll
+    for (int i = 0; i < N; ++i) acc[i] = 0.f;
+    for (int s = 0; s < K; ++s) {
+      const int peer = nbr[j * K + s];
+      Vec16<T> qs;
+      qs.load(src + (long)peer * elems + v * N);
+      float f[N];
+      qs.unpack(f);
+#pragma unroll
+      for (int i = 0; i < N; ++i) acc[i] += f[i] - f0[i];
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) acc[i] = fmaf(scale, acc[i], f0[i]);
+    q.pack(acc);
+    q.store(dst + (long)j * elems + v * N);
+  }
+}
+
+inline int ok() { return hipGetLastError() == hipSuccess ? SPES_OK : SPES_EHIP; }
+
+inline int stream_grid_x(long nvec) {
+  long b = (nvec + 256L * 4 - 1) / (256L * 4);
+  if (b < 1) b = 1;
+  if (b > 4096) b = 4096;
+  return (int)b;
+}
+
+template <typename T>
+int flush(const MergeTable& tb, int n, void* dst, long elems, hipStream_t s) {
+  if (n == 0) return SPES_OK;
+  const long nvec = elems / Vec16<T>::N;
+  hipLaunchKernelGGL(sync_merge_kernel<T>, dim3(stream_grid_x(nvec), n), dim3(256), 0, s, tb, (T*)dst, nvec);
+  return ok();
+}
+
+}  // namespace
+
+int launch_sync_merge(int dtype, int n_experts, long elems, int n_nodes, const void* const* node_store, const int* slot,
+                      const float* node_weight, void* dst, int* trainer_count, hipStream_t s) {
+  const size_t es = dtype == SPES_F32 ? 4 : 2;
+  MergeTable tb;
+  int n_in = 0, n_ent = 0;
+  tb.first[0] = 0;
+  std::vector<unsigned char> counts(n_experts, 0);
+  for (int j = 0; j < n_experts; ++j) {
+    int n = 0;
+    double wsum = 0.0;
+    for (int i = 0; i < n_nodes; ++i)
+      if (slot[(long)i * n_experts + j] >= 0) { ++n; wsum += node_weight ? (double)node_weight[i] : 1.0; }
+    counts[j] = (unsigned char)n;
+    if (n == 0) continue;
+    if (n_in == kMergeExperts || n_ent + n > kMergeEntries) {
+      int rc = dtype == SPES_F32 ? flush<float>(tb, n_in, dst, elems, s) : flush<bf16_t>(tb, n_in, dst, elems, s);
+      if (rc != SPES_OK) return rc;
+      n_in = 0; n_ent = 0;
+    }
+    for (int i = 0; i < n_nodes; ++i) {
+      const int sl = slot[(long)i * n_experts + j];
+      if (sl < 0) continue;
+      tb.src[n_ent] = static_cast<const char*>(node_store[i]) + (size_t)sl * elems * es;
+      tb.w[n_ent] = (float)((node_weight ? (double)node_weight[i] : 1.0) / wsum);
+      ++n_ent;
+    }
+    tb.dst_off[n_in] = (long)j * elems;
+    tb.first[++n_in] = n_ent;
+  }
+  int rc = dtype == SPES_F32 ? flush<float>(tb, n_in, dst, elems, s) : flush<bf16_t>(tb, n_in, dst, elems, s);
+  if (rc != SPES_OK) return rc;
+  if (trainer_count != nullptr) {
+    for (int base = 0; base < n_experts; base += 1024) {
+      CountTable ct;
+      ct.base = base;
+      ct.n = n_experts - base < 1024 ? n_experts - base : 1024;
+      for (int i = 0; i < ct.n; ++i) ct.c[i] = counts[base + i];
+      hipLaunchKernelGGL(write_counts_kernel, dim3(cdiv(ct.n, 256)), dim3(256), 0, s, ct, trainer_count);
+    }
+    if (ok() != SPES_OK) return SPES_EHIP;
+  }
+  return SPES_OK;
+}
+
+int launch_sim_topk(const float* partial, int n_partial, int M, int K, float* sim, int* nbr, hipStream_t s) {
+  hipLaunchKernelGGL(sim_topk_kernel, dim3(1), dim3(256), 0, s, partial, n_partial, M, K, sim, nbr);
+  return ok();
+}
+
+int launch_warmup_mix(int dtype, int M, long elems, int K, float alpha, const void* src, void* dst, const int* nbr, hipStream_t s) {
+  const float scale = alpha / (float)K;
+  if (dtype == SPES_F32) {
+    const long nvec = elems / 4;
+    hipLaunchKernelGGL(warmup_mix_kernel<float>, dim3(stream_grid_x(nvec), M), dim3(256), 0, s, (const float*)src, (float*)dst,
+                       nbr, K, scale, nvec, elems);
+  } else {
+    const long nvec = elems / 8;
+    hipLaunchKernelGGL(warmup_mix_kernel<bf16_t>, dim3(stream_grid_x(nvec), M), dim3(256), 0, s, (const bf16_t*)src,
+                       (bf16_t*)dst, nbr, K, scale, nvec, elems);
+  }
+  return ok();
+}
+
+}  // namespace spes

@@ -1,0 +1,185 @@
+// Bandwidth-bound row movement around the expert GEMMs: gather into
+// expert-contiguous order, gate-weighted combine (Eq. 2), and their backward
+// counterparts.  All traffic is 16-byte vectors along the contiguous feature
+// dimension; sums run in fp32 in a fixed slot order and are rounded once.
+#include "kernels.h"
+
+namespace spes {
+namespace {
+
+// xp[r,:] = x[perm[r] / k, :]
+template <typename T>
+__global__ __launch_bounds__(256) void permute_kernel(const T* __restrict__ x, const int* __restrict__ perm, int k,
+                                                      T* __restrict__ xp, long total_vec, int nvec, int d) {
+  constexpr int N = Vec16<T>::N;
+  const long stride = (long)gridDim.x * 256;
+  for (long v = (long)blockIdx.x * 256 + threadIdx.x; v < total_vec; v += stride) {
+    const long r = v / nvec;
+    const int c = (int)(v - r * nvec);
+    const int t = perm[r] / k;
+    Vec16<T> q;
+    q.load(x + (long)t * d + c * N);
+    q.store(xp + r * d + c * N);
+  }
+}
+
+// y[t,:] = sum_j gate[t,j] * yp[inv[t*k+j], :]
+template <typename T>
+__global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ yp, const int* __restrict__ inv,
+                                                      const float* __restrict__ gate, T* __restrict__ y, long total_vec,
+                                                      int nvec, int d, int k) {
+  constexpr int N = Vec16<T>::N;
+  const long stride = (long)gridDim.x * 256;
+  for (long v = (long)blockIdx.x * 256 + threadIdx.x; v < total_vec; v += stride) {
+    const long t = v / nvec;
+    const int c = (int)(v - t * nvec);
+    float acc[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) acc[i] = 0.f;
+    for (int j = 0; j < k; ++j) {
+      const long r = inv[t * k + j];
+      const float g = gate[t * k + j];
+      Vec16<T> q;
+      q.load(yp + r * d + c * N);
+      float f[N];
+      q.unpack(f);
+#pragma unroll
+      for (int i = 0; i < N; ++i) acc[i] = fmaf(g, f[i], acc[i]);
+    }
+    Vec16<T> o;
+    o.pack(acc);
+    o.store(y + t * d + c * N);
+  }
+}
+
+// dyp[r,:] = gate[t,j] * dy[t,:] and dgate[t,j] = <dy[t,:], yp[r,:]>, r = inv[t*k+j]; one block per token
+template <typename T>
+__global__ __launch_bounds__(256) void dy_scatter_kernel(const T* __restrict__ dy, const T* __restrict__ yp,
+                                                         const int* __restrict__ inv, const float* __restrict__ gate,
+                                                         T* __restrict__ dyp, float* __restrict__ dgate, int d, int k) {
+  constexpr int N = Vec16<T>::N;
+  __shared__ float red[4];
+  const long t = blockIdx.x;
+  const int nvec = d / N;
+  for (int j = 0; j < k; ++j) {
+    const long r = inv[t * k + j];
+    const float g = gate[t * k + j];
+    float part = 0.f;
+    for (int c = threadIdx.x; c < nvec; c += 256) {
+      Vec16<T> a, b, o;
+      a.load(dy + t * d + c * N);
+      b.load(yp + r * d + c * N);
+      float fa[N], fb[N], fo[N];
+      a.unpack(fa);
+      b.unpack(fb);
+#pragma unroll
+      for (int i = 0; i < N; ++i) { fo[i] = g * fa[i]; part = fmaf(fa[i], fb[i], part); }
+      o.pack(fo);
+      o.store(dyp + r * d + c * N);
+    }
+    const float tot = block_sum_256(part, red);
+    if (threadIdx.x == 0) dgate[t * k + j] = tot;
+  }
+}
+
+// dx[t,:] = sum_j dxp[inv[t*k+j], :] + sum_e dlogits[t,e] * w_router[e,:]; one block per token
+template <typename T>
+__global__ __launch_bounds__(256) void dx_gather_kernel(const T* __restrict__ dxp, const int* __restrict__ inv,
+                                                        const float* __restrict__ dlogits, const T* __restrict__ w_router,
+                                                        T* __restrict__ dx, int d, int k, int M) {
+  constexpr int N = Vec16<T>::N;
+  __shared__ float dl[kMaxExperts];
+  __shared__ int rows[kMaxExperts];
+  const long t = blockIdx.x;
+  if (threadIdx.x < M) dl[threadIdx.x] = dlogits[t * M + threadIdx.x];
+  if (threadIdx.x < k) rows[threadIdx.x] = inv[t * k + threadIdx.x];
+  __syncthreads();
+  const int nvec = d / N;
+  for (int c = threadIdx.x; c < nvec; c += 256) {
+    float acc[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) acc[i] = 0.f;
+    for (int j = 0; j < k; ++j) {
+      Vec16<T> q;
+      q.load(dxp + (long)rows[j] * d + c * N);
+      float f[N];
+      q.unpack(f);
+#pragma unroll
+      for (int i = 0; i < N; ++i) acc[i] += f[i];
+    }
+    for (int e = 0; e < M; ++e) {
+      Vec16<T> q;
+      q.load(w_router + (long)e * d + c * N);
+      float f[N];
+      q.unpack(f);
+      const float s = dl[e];
+#pragma unroll
+      for (int i = 0; i < N; ++i) acc[i] = fmaf(s, f[i], acc[i]);
+    }
+    Vec16<T> o;
+    o.pack(acc);
+    o.store(dx + t * d + c * N);
+  }
+}
+
+inline int flat_grid(long total_vec) {
+  long b = (total_vec + 256L * 4 - 1) / (256L * 4);
+  if (b < 1) b = 1;
+  if (b > 1 << 20) b = 1 << 20;
+  return (int)b;
+}
+
+inline int ok() { return hipGetLastError() == hipSuccess ? SPES_OK : SPES_EHIP; }
+
+}  // namespace
+
+int launch_permute(int dtype, const void* x, const int* perm, int k, void* xp, long R, int d, hipStream_t s) {
+  if (R == 0) return SPES_OK;
+  if (dtype == SPES_F32) {
+    const int nvec = d / 4;
+    hipLaunchKernelGGL(permute_kernel<float>, dim3(flat_grid(R * nvec)), dim3(256), 0, s, (const float*)x, perm, k, (float*)xp,
+                       R * nvec, nvec, d);
+  } else {
+    const int nvec = d / 8;
+    hipLaunchKernelGGL(permute_kernel<bf16_t>, dim3(flat_grid(R * nvec)), dim3(256), 0, s, (const bf16_t*)x, perm, k,
+                       (bf16_t*)xp, R * nvec, nvec, d);
+  }
+  return ok();
+}
+
+int launch_combine(int dtype, const void* yp, const int* inv, const float* gate, void* y, int T, int d, int k, hipStream_t s) {
+  if (dtype == SPES_F32) {
+    const int nvec = d / 4;
+    hipLaunchKernelGGL(combine_kernel<float>, dim3(flat_grid((long)T * nvec)), dim3(256), 0, s, (const float*)yp, inv, gate,
+                       (float*)y, (long)T * nvec, nvec, d, k);
+  } else {
+    const int nvec = d / 8;
+    hipLaunchKernelGGL(combine_kernel<bf16_t>, dim3(flat_grid((long)T * nvec)), dim3(256), 0, s, (const bf16_t*)yp, inv, gate,
+                       (bf16_t*)y, (long)T * nvec, nvec, d, k);
+  }
+  return ok();
+}
+
+int launch_dy_scatter(int dtype, const void* dy, const void* yp, const int* inv, const float* gate, void* dyp, float* dgate,
+                      int T, int d, int k, hipStream_t s) {
+  if (dtype == SPES_F32)
+    hipLaunchKernelGGL(dy_scatter_kernel<float>, dim3(T), dim3(256), 0, s, (const float*)dy, (const float*)yp, inv, gate,
+                       (float*)dyp, dgate, d, k);
+  else
+    hipLaunchKernelGGL(dy_scatter_kernel<bf16_t>, dim3(T), dim3(256), 0, s, (const bf16_t*)dy, (const bf16_t*)yp, inv, gate,
+                       (bf16_t*)dyp, dgate, d, k);
+  return ok();
+}
+
+int launch_dx_gather(int dtype, const void* dxp, const int* inv, const float* dlogits, const void* w_router, void* dx, int T,
+                     int d, int k, int M, hipStream_t s) {
+  if (dtype == SPES_F32)
+    hipLaunchKernelGGL(dx_gather_kernel<float>, dim3(T), dim3(256), 0, s, (const float*)dxp, inv, dlogits,
+                       (const float*)w_router, (float*)dx, d, k, M);
+  else
+    hipLaunchKernelGGL(dx_gather_kernel<bf16_t>, dim3(T), dim3(256), 0, s, (const bf16_t*)dxp, inv, dlogits,
+                       (const bf16_t*)w_router, (bf16_t*)dx, d, k, M);
+  return ok();
+}
+
+}  // namespace spes

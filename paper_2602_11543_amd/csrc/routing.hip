@@ -1,0 +1,218 @@
+// Routing: softmax/top-k gating, per-expert histogram, prefix scan and the
+// stable permutation into expert-contiguous order (paper Sec. 3.2: softmax
+// routing, drop-less dispatch).  Integer results are deterministic: no
+// order-dependent atomics decide a position.
+#include "kernels.h"
+
+namespace spes {
+namespace {
+
+// One wavefront per token, one router score per lane.
+__global__ __launch_bounds__(256) void topk_gate_kernel(float* __restrict__ logits, const float* __restrict__ bias,
+                                                        int T, int M, int k, int renorm, int* __restrict__ topk_idx,
+                                                        float* __restrict__ topk_gate, int* __restrict__ idx_copy,
+                                                        float* __restrict__ gate_copy, float* __restrict__ lse) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  float s = -INFINITY;
+  if (lane < M) {
+    s = logits[(long)t * M + lane];
+    if (bias != nullptr) {
+      s += bias[lane];
+      logits[(long)t * M + lane] = s;   // the backward recomputes probabilities from the biased score
+    }
+  }
+  const float mx = wave_max(s);
+  const float ex = (lane < M) ? expf(s - mx) : 0.f;
+  const float sum = wave_sum(ex);
+  const float p = ex / sum;
+  if (lane == 0) lse[t] = mx + logf(sum);
+
+  bool taken = false;
+  int my_idx = 0;
+  float my_p = 0.f, psel = 0.f;
+  for (int j = 0; j < k; ++j) {
+    float v = taken ? -INFINITY : s;
+    int i = lane;
+    wave_argmax(v, i);                     // selection on the scores: ties go to the lower expert id
+    if (lane == i) taken = true;
+    const float pw = __shfl(p, i, kWave);
+    psel += pw;
+    if (lane == j) { my_idx = i; my_p = pw; }
+  }
+  if (lane < k) {
+    const float g = renorm ? my_p / psel : my_p;
+    topk_idx[(long)t * k + lane] = my_idx;
+    topk_gate[(long)t * k + lane] = g;
+    idx_copy[(long)t * k + lane] = my_idx;
+    gate_copy[(long)t * k + lane] = g;
+  }
+}
+
+constexpr int kRankItems = 8;
+constexpr int kRankChunk = 256 * kRankItems;   // routed pairs per block
+
+__global__ __launch_bounds__(256) void count_kernel(const int* __restrict__ idx, int R, int* __restrict__ block_counts) {
+  __shared__ int h[kMaxExperts];
+  if (threadIdx.x < kMaxExperts) h[threadIdx.x] = 0;
+  __syncthreads();
+  const long base = (long)blockIdx.x * kRankChunk;
+#pragma unroll
+  for (int i = 0; i < kRankItems; ++i) {
+    const long flat = base + i * 256 + threadIdx.x;
+    if (flat < R) atomicAdd(&h[idx[flat]], 1);
+  }
+  __syncthreads();
+  if (threadIdx.x < kMaxExperts) block_counts[blockIdx.x * kMaxExperts + threadIdx.x] = h[threadIdx.x];
+}
+
+__device__ __forceinline__ int wave_exclusive_scan(int v, int lane) {
+  int inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int n = __shfl_up(inc, o, kWave);
+    if (lane >= o) inc += n;
+  }
+  return inc - v;
+}
+
+// One wavefront: lane e owns expert e.  Turns per-block counts into per-block
+// first positions, and writes counts, offsets and the row-tile tables.
+__global__ __launch_bounds__(64) void scan_kernel(int* __restrict__ block_counts, int nblk, int M, int* __restrict__ expert_count,
+                                                  int* __restrict__ offset, int bm0, int* __restrict__ tab0, int bm1,
+                                                  int* __restrict__ tab1, int max_tiles) {
+  const int e = threadIdx.x;
+  int total = 0;
+  for (int b = 0; b < nblk; ++b) total += block_counts[b * kMaxExperts + e];
+  const int off = wave_exclusive_scan(total, e);
+  int running = off;
+  for (int b = 0; b < nblk; ++b) {
+    const int c = block_counts[b * kMaxExperts + e];
+    block_counts[b * kMaxExperts + e] = running;
+    running += c;
+  }
+  if (e < M) { expert_count[e] = total; offset[e] = off; }
+  if (e == M - 1) offset[M] = off + total;
+  // table layout: [0] = number of tiles, [1 .. max_tiles] expert of each tile, [1+max_tiles ..] first row
+  for (int which = 0; which < 2; ++which) {
+    const int bm = which ? bm1 : bm0;
+    int* tab = which ? tab1 : tab0;
+    if (bm <= 0 || tab == nullptr) continue;
+    const int nt = (total + bm - 1) / bm;
+    const int t0 = wave_exclusive_scan(nt, e);
+    for (int i = 0; i < nt; ++i) {
+      tab[1 + t0 + i] = e;
+      tab[1 + max_tiles + t0 + i] = off + i * bm;
+    }
+    if (e == 63) tab[0] = t0 + nt;
+  }
+}
+
+__global__ __launch_bounds__(256) void scatter_kernel(const int* __restrict__ idx, int R, const int* __restrict__ block_base,
+                                                      int* __restrict__ perm, int* __restrict__ inv) {
+  __shared__ int running[kMaxExperts];
+  __shared__ int wcnt[4][kMaxExperts];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  if (tid < kMaxExperts) {
+    running[tid] = block_base[blockIdx.x * kMaxExperts + tid];
+    wcnt[0][tid] = wcnt[1][tid] = wcnt[2][tid] = wcnt[3][tid] = 0;
+  }
+  __syncthreads();
+  const long base = (long)blockIdx.x * kRankChunk;
+  const unsigned long long lt = (1ull << lane) - 1ull;
+  for (int i = 0; i < kRankItems; ++i) {
+    const long flat = base + i * 256 + tid;
+    const bool valid = flat < R;
+    const int e = valid ? idx[flat] : 0;
+    // lanes of this wavefront routed to the same expert
+    unsigned long long peers = __ballot(valid);
+#pragma unroll
+    for (int b = 0; b < 6; ++b) {
+      const bool bit = (e >> b) & 1;
+      const unsigned long long m = __ballot(valid && bit);
+      peers &= bit ? m : ~m;
+    }
+    const int rank = __popcll(peers & lt);
+    if (valid && rank == 0) wcnt[w][e] = __popcll(peers);
+    __syncthreads();
+    if (valid) {
+      int r = running[e] + rank;
+      for (int ww = 0; ww < w; ++ww) r += wcnt[ww][e];
+      perm[r] = (int)flat;
+      inv[flat] = r;
+    }
+    __syncthreads();
+    if (tid < kMaxExperts) {
+      running[tid] += wcnt[0][tid] + wcnt[1][tid] + wcnt[2][tid] + wcnt[3][tid];
+      wcnt[0][tid] = wcnt[1][tid] = wcnt[2][tid] = wcnt[3][tid] = 0;
+    }
+    __syncthreads();
+  }
+}
+
+// dlogits from dgate (one wavefront per token).  renorm=0: softmax Jacobian on
+// the sparse dp; renorm=1: the renormalised gates are a softmax over the
+// selected scores alone.
+__global__ __launch_bounds__(256) void gating_bwd_kernel(const float* __restrict__ logits, const float* __restrict__ lse,
+                                                         const int* __restrict__ topk_idx, const float* __restrict__ topk_gate,
+                                                         const float* __restrict__ dgate, int T, int M, int k, int renorm,
+                                                         float* __restrict__ dlogits) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  // lane j < k holds selected pair j
+  int sel = -1; float g = 0.f, dg = 0.f;
+  if (lane < k) { sel = topk_idx[(long)t * k + lane]; g = topk_gate[(long)t * k + lane]; dg = dgate[(long)t * k + lane]; }
+  float out = 0.f;
+  if (renorm) {
+    const float dot = wave_sum(g * dg);
+    const float mine = g * (dg - dot);
+    // scatter lane j's value to lane sel
+    for (int j = 0; j < k; ++j) {
+      const int ej = __shfl(sel, j, kWave);
+      const float vj = __shfl(mine, j, kWave);
+      if (lane == ej) out = vj;
+    }
+  } else {
+    const float p = (lane < M) ? expf(logits[(long)t * M + lane] - lse[t]) : 0.f;
+    float dp = 0.f;
+    for (int j = 0; j < k; ++j) {
+      const int ej = __shfl(sel, j, kWave);
+      const float vj = __shfl(dg, j, kWave);
+      if (lane == ej) dp = vj;
+    }
+    const float dot = wave_sum(dp * p);
+    out = p * (dp - dot);
+  }
+  if (lane < M) dlogits[(long)t * M + lane] = out;
+}
+
+}  // namespace
+
+int routing_blocks(int R) { return cdiv(R, kRankChunk); }
+
+int launch_topk_gate(float* logits, const float* bias, int T, int M, int k, int renorm, int* idx, float* gate, int* idx_copy,
+                     float* gate_copy, float* lse, hipStream_t s) {
+  hipLaunchKernelGGL(topk_gate_kernel, dim3(cdiv(T, 4)), dim3(256), 0, s, logits, bias, T, M, k, renorm, idx, gate, idx_copy,
+                     gate_copy, lse);
+  return hipGetLastError() == hipSuccess ? SPES_OK : SPES_EHIP;
+}
+
+int launch_routing_tables(const int* idx, int R, int M, int* block_counts, int* expert_count, int* offset, int* perm,
+                          int* inv, int bm0, int* tab0, int bm1, int* tab1, int max_tiles, hipStream_t s) {
+  const int nblk = routing_blocks(R);
+  hipLaunchKernelGGL(count_kernel, dim3(nblk), dim3(256), 0, s, idx, R, block_counts);
+  hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(64), 0, s, block_counts, nblk, M, expert_count, offset, bm0, tab0, bm1, tab1,
+                     max_tiles);
+  hipLaunchKernelGGL(scatter_kernel, dim3(nblk), dim3(256), 0, s, idx, R, block_counts, perm, inv);
+  return hipGetLastError() == hipSuccess ? SPES_OK : SPES_EHIP;
+}
+
+int launch_gating_bwd(const float* logits, const float* lse, const int* idx, const float* gate, const float* dgate, int T, int M,
+                      int k, int renorm, float* dlogits, hipStream_t s) {
+  hipLaunchKernelGGL(gating_bwd_kernel, dim3(cdiv(T, 4)), dim3(256), 0, s, logits, lse, idx, gate, dgate, T, M, k, renorm, dlogits);
+  return hipGetLastError() == hipSuccess ? SPES_OK : SPES_EHIP;
+}
+
+}  // namespace spes

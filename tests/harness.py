@@ -1,0 +1,90 @@
+"""Shared helpers of the GPU parity tests: run the HIP path through the C ABI, compare with the oracle."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2602_11543_amd as S
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}     # max |a-b| / max |b| per tensor (stated by the benchmark definition)
+
+
+def rel_err(got, want) -> float:
+    got = np.asarray(got, dtype=np.float64); want = np.asarray(want, dtype=np.float64)
+    den = np.abs(want).max()
+    return float(np.abs(got - want).max() / (den if den > 0 else 1.0))
+
+
+def to_dev(a: np.ndarray, dtype: str, device) -> torch.Tensor:
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype == "bf16":
+        t = t.to(torch.bfloat16)          # exact: the generator already rounded to bf16
+    return t.to(device)
+
+
+def shape_of(cfg) -> "S.spes_moe_shape":
+    return S.moe_shape(cfg.T, cfg.d, cfg.M, cfg.f, cfg.k, S.SPES_F32 if cfg.dtype == "f32" else S.SPES_BF16, cfg.renorm)
+
+
+class DeviceLayer:
+    """Device copies of one layer's inputs plus the output/ctx buffers of fwd and bwd."""
+
+    def __init__(self, inp: dict, device, mask=None):
+        cfg = inp["cfg"]
+        self.cfg, self.shape, self.dev = cfg, shape_of(cfg), device
+        dt = cfg.dtype
+        self.x = to_dev(inp["x"], dt, device); self.dy = to_dev(inp["dy"], dt, device)
+        self.w_router = to_dev(inp["w_router"], dt, device)
+        self.bias = None if inp["router_bias"] is None else torch.from_numpy(inp["router_bias"]).to(device)
+        self.w_gate = to_dev(inp["w_gate"], dt, device); self.w_up = to_dev(inp["w_up"], dt, device)
+        self.w_down = to_dev(inp["w_down"], dt, device)
+        st = S.torch_dtype(self.shape.dtype)
+        T, d, M, f, k = cfg.T, cfg.d, cfg.M, cfg.f, cfg.k
+        self.y = torch.empty(T, d, dtype=st, device=device)
+        self.idx = torch.empty(T, k, dtype=torch.int32, device=device)
+        self.gate = torch.empty(T, k, dtype=torch.float32, device=device)
+        self.count = torch.empty(M, dtype=torch.int32, device=device)
+        self.ctx = torch.empty(S.spes_moe_ctx_bytes(self.shape), dtype=torch.uint8, device=device)
+        self.dx = torch.empty(T, d, dtype=st, device=device)
+        self.d_w_router = torch.zeros(M, d, dtype=torch.float32, device=device)
+        self.set_mask(inp["trainable_mask"] if mask is None else mask)
+
+    def set_mask(self, mask):
+        cfg = self.cfg
+        self.mask = np.asarray(mask, dtype=np.uint8)
+        n = int(self.mask.sum())
+        self.trainable = [int(e) for e in np.nonzero(self.mask)[0]]
+        mk = lambda *s: torch.zeros(*s, dtype=torch.float32, device=self.dev) if n else None
+        self.d_w_gate, self.d_w_up, self.d_w_down = mk(n, cfg.f, cfg.d), mk(n, cfg.f, cfg.d), mk(n, cfg.d, cfg.f)
+
+    def fwd(self):
+        S.spes_moe_fwd(self.shape, self.x, self.w_router, self.bias, self.w_gate, self.w_up, self.w_down, self.y, self.idx,
+                       self.gate, self.count, self.ctx)
+
+    def bwd(self, accumulate=0):
+        S.spes_moe_bwd(self.shape, self.dy, self.x, self.w_router, self.w_gate, self.w_up, self.w_down, self.ctx, self.mask,
+                       self.dx, self.d_w_router, self.d_w_gate, self.d_w_up, self.d_w_down, accumulate)
+
+    def view(self, name):
+        return S.ctx_view(self.shape, self.ctx, name)
+
+    def host(self, t):
+        return t.float().cpu().numpy() if t.dtype == torch.bfloat16 else t.cpu().numpy()
+
+
+def oracle_run(inp, O, keep=True):
+    cfg = inp["cfg"]
+    fwd = O.moe_forward(inp["x"], inp["w_router"], inp["router_bias"], inp["w_gate"], inp["w_up"], inp["w_down"],
+                        cfg.k, cfg.renorm, keep=keep)
+    return fwd
+
+
+def check_routing(L: DeviceLayer, fwd) -> None:
+    """Integer routing results are compared bit for bit."""
+    cfg = L.cfg
+    assert np.array_equal(L.idx.cpu().numpy(), fwd["idx"]), "top-k indices differ"
+    assert np.array_equal(L.count.cpu().numpy(), fwd["count"]), "per-expert counts differ"
+    assert np.array_equal(L.view("offset").cpu().numpy(), fwd["offset"])
+    assert np.array_equal(L.view("perm").cpu().numpy(), fwd["perm"]), "permutation differs"
+    assert np.array_equal(L.view("inv").cpu().numpy(), fwd["inv"])
+    assert int(L.count.sum()) == cfg.T * cfg.k
