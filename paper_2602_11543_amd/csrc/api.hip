@@ -10,8 +10,8 @@ namespace {
 
 struct Layout {
   spes_moe_ctx_layout pub;
-  size_t block_counts, tab_simt, tab_mfma, dyp, da, db, dxp;
-  int max_tiles;
+  size_t block_counts, tab_simt, tab_mfma, row_token, row_gate, dgate_part, da, db, dxp;
+  int max_tiles, max_col_tiles;
 };
 
 bool shape_ok(const spes_moe_shape* s) {
@@ -48,14 +48,17 @@ Layout make_layout(const spes_moe_shape* s) {
   L.block_counts = take((size_t)routing_blocks((int)R) * kMaxExperts * 4);
   L.tab_simt = take((1 + 2 * (size_t)L.max_tiles) * 4);
   L.tab_mfma = take((1 + 2 * (size_t)L.max_tiles) * 4);
+  L.row_token = take(R * 4);
+  L.row_gate = take(R * 4);
   L.pub.xp = take(R * d * es);
-  L.pub.a = take(R * f * es);
-  L.pub.b = take(R * f * es);
+  L.pub.a = take(R * f * 4);
+  L.pub.b = take(R * f * 4);
   L.pub.h = take(R * f * es);
   L.pub.yp = take(R * d * es);
   L.pub.dlogits = take(T * M * 4);
   L.pub.dgate = take(T * k * 4);
-  L.dyp = take(R * d * es);
+  L.max_col_tiles = cdiv((long)f, 64);
+  L.dgate_part = take((size_t)L.max_col_tiles * R * 4);
   L.da = take(R * f * es);
   L.db = take(R * f * es);
   L.dxp = take(R * d * es);
@@ -127,10 +130,11 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
   }
   SPES_TRY(launch_topk_gate(at<float>(ctx, L.pub.logits), router_bias, T, M, k, shape->renorm_topk, topk_idx, topk_gate,
                             at<int>(ctx, L.pub.topk_idx), at<float>(ctx, L.pub.topk_gate), at<float>(ctx, L.pub.lse), s));
-  SPES_TRY(launch_routing_tables(topk_idx, (int)R, M, at<int>(ctx, L.block_counts), expert_count, at<int>(ctx, L.pub.offset),
-                                 at<int>(ctx, L.pub.perm), at<int>(ctx, L.pub.inv), simt_row_tile(), at<int>(ctx, L.tab_simt), 0,
-                                 at<int>(ctx, L.tab_mfma), L.max_tiles, s));
-  SPES_TRY(launch_permute(dt, x, at<int>(ctx, L.pub.perm), k, at<void>(ctx, L.pub.xp), R, d, s));
+  SPES_TRY(launch_routing_tables(topk_idx, topk_gate, (int)R, M, k, at<int>(ctx, L.block_counts), expert_count,
+                                 at<int>(ctx, L.pub.offset), at<int>(ctx, L.pub.perm), at<int>(ctx, L.pub.inv),
+                                 at<int>(ctx, L.row_token), at<float>(ctx, L.row_gate), simt_row_tile(),
+                                 at<int>(ctx, L.tab_simt), 0, at<int>(ctx, L.tab_mfma), L.max_tiles, s));
+  SPES_TRY(launch_permute(dt, x, at<int>(ctx, L.row_token), at<void>(ctx, L.pub.xp), R, d, s));
   // a = xp W_g^T, b = xp W_u^T, h = SiLU(a) * b
   {
     GemmArgs g = blank();
@@ -177,22 +181,25 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
   const float* gate = at<float>(ctx, L.pub.topk_gate);   // the forward's own copies: its outputs belong to the caller
   const int* idx = at<int>(ctx, L.pub.topk_idx);
 
-  // dyp = gate * dy (expert-contiguous), dgate = <dy, yp>
-  SPES_TRY(launch_dy_scatter(dt, dy, at<void>(ctx, L.pub.yp), inv, gate, at<void>(ctx, L.dyp), at<float>(ctx, L.pub.dgate), T, d,
-                             k, s));
-  SPES_TRY(launch_gating_bwd(at<float>(ctx, L.pub.logits), at<float>(ctx, L.pub.lse), idx, gate, at<float>(ctx, L.pub.dgate), T,
-                             M, k, shape->renorm_topk, at<float>(ctx, L.pub.dlogits), s));
-  // dh = dyp W_d, then da, db through the SwiGLU
+  // u = dy[token] W_d per routed row; its epilogue yields the gate gradient <u, h> (per column tile) and,
+  // through the SwiGLU, da and db of the gate-scaled upstream gradient
+  const long R = (long)T * k;
+  const int n_part = cdiv(f, simt_col_tile());
   {
     GemmArgs g = blank();
-    g.A[0] = at<void>(ctx, L.dyp); g.a_ms = d; g.a_ks = 1;
+    g.A[0] = dy; g.a_ms = d; g.a_ks = 1; g.a_rows = at<int>(ctx, L.row_token);
     g.B[0] = w_down; g.b_ns = 1; g.b_ks = f; g.b_gs = (long)d * f;
     g.Kdim = d; g.Ndim = f;
     g.E[0] = at<void>(ctx, L.pub.a); g.E[1] = at<void>(ctx, L.pub.b);
     g.C[0] = at<void>(ctx, L.da); g.C[1] = at<void>(ctx, L.db); g.c_ms = f;
+    g.row_scale = at<float>(ctx, L.row_gate);
+    g.rowdot = at<float>(ctx, L.dgate_part); g.rowdot_stride = R;
     ragged_tables(g, ctx, L);
     SPES_TRY(launch_gemm_simt(dt, dt, kRaggedM, kEpiDSwiglu, g, s));
   }
+  SPES_TRY(launch_gating_bwd(at<float>(ctx, L.pub.logits), at<float>(ctx, L.pub.lse), idx, gate, at<float>(ctx, L.dgate_part),
+                             n_part, R, inv, at<float>(ctx, L.pub.dgate), T, M, k, shape->renorm_topk,
+                             at<float>(ctx, L.pub.dlogits), s));
   // dxp = da W_g + db W_u
   {
     GemmArgs g = blank();
@@ -211,14 +218,14 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
     memcpy(g.group_expert, train_list, n_train);
     g.offset = at<int>(ctx, L.pub.offset);
     g.c_f32 = 1; g.accumulate = accumulate;
-    // dW_d[d,f] = dyp^T h
-    g.A[0] = at<void>(ctx, L.dyp); g.a_ms = 1; g.a_ks = d;
+    // dW_d[d,f] = (gate * dy[token])^T h over the expert's rows
+    g.A[0] = dy; g.a_ms = 1; g.a_ks = d; g.a_rows = at<int>(ctx, L.row_token); g.a_scale = at<float>(ctx, L.row_gate);
     g.B[0] = at<void>(ctx, L.pub.h); g.b_ns = 1; g.b_ks = f;
     g.Mdim = d; g.Ndim = f; g.C[0] = d_w_down; g.c_ms = f; g.c_gs = (long)d * f;
     SPES_TRY(launch_gemm_simt(dt, dt, kGroupedK, kEpiStore, g, s));
     // dW_g[f,d] = da^T xp ; dW_u[f,d] = db^T xp
     g.B[0] = at<void>(ctx, L.pub.xp); g.b_ns = 1; g.b_ks = d;
-    g.a_ms = 1; g.a_ks = f; g.Mdim = f; g.Ndim = d; g.c_ms = d; g.c_gs = (long)f * d;
+    g.a_ms = 1; g.a_ks = f; g.a_rows = nullptr; g.a_scale = nullptr; g.Mdim = f; g.Ndim = d; g.c_ms = d; g.c_gs = (long)f * d;
     g.A[0] = at<void>(ctx, L.da); g.C[0] = d_w_gate;
     SPES_TRY(launch_gemm_simt(dt, dt, kGroupedK, kEpiStore, g, s));
     g.A[0] = at<void>(ctx, L.db); g.C[0] = d_w_up;

@@ -17,14 +17,21 @@ namespace spes {
 enum GemmMode { kRaggedM = 0, kGroupedK = 1 };
 enum GemmEpi {
   kEpiStore = 0,    // C[0] = acc (or += when accumulate)
-  kEpiSwiglu = 1,   // two accumulators a (pair 0), b (pair 1): C[0]=a, C[1]=b, C[2]=SiLU(a)*b
-  kEpiDSwiglu = 2   // acc = dh; with saved a=E[0], b=E[1]: C[0]=da, C[1]=db
+  kEpiSwiglu = 1,   // two accumulators a (pair 0), b (pair 1): C[0]=a (f32), C[1]=b (f32), C[2]=SiLU(a)*b
+  kEpiDSwiglu = 2   // acc = u (row of dy times W_d); with saved a=E[0], b=E[1] (f32), h = SiLU(a)*b:
+                    //   rowdot[tile_n][m] = sum_n u*h (the gate gradient), dh = row_scale[m]*u,
+                    //   C[0] = da = dh*b*s(1+a(1-s)), C[1] = db = dh*a*s, s = sigmoid(a)
 };
 
 struct GemmArgs {
   const void* A[2];
   const void* B[2];
   long a_ms, a_ks;        // element strides of A along m, k
+  const int* a_rows;      // optional gather: kRaggedM reads row a_rows[m] in place of m; kGroupedK reads row a_rows[k] in place of k
+  const float* a_scale;   // optional (kGroupedK): A(m,k) is multiplied by a_scale[k]
+  const float* row_scale; // kEpiDSwiglu: per-row factor (the gate of the routed pair)
+  float* rowdot;          // kEpiDSwiglu: [gridDim.x, rowdot_stride] partial gate gradients
+  long rowdot_stride;
   long b_ns, b_ks, b_gs;  // element strides of B along n, k, and per expert (kRaggedM)
   int npairs;             // kEpiStore/kEpiDSwiglu: (A,B) pairs accumulated into one result
   int Kdim;               // contraction length of each pair (kRaggedM) / total K (kGroupedK, uniform chunks)

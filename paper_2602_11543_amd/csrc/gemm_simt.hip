@@ -21,6 +21,7 @@ __global__ __launch_bounds__(256) void gemm_simt_kernel(const GemmArgs g) {
   constexpr bool DUAL = (EPI == kEpiSwiglu);
   __shared__ float As[BK][BM + 4];
   __shared__ float Bs[DUAL ? 2 : 1][BK][BN + 4];
+  __shared__ float Red[EPI == kEpiDSwiglu ? BM : 1][17];
 
   const int tid = threadIdx.x;
   const int tx = tid & 15, ty = tid >> 4;
@@ -69,7 +70,18 @@ __global__ __launch_bounds__(256) void gemm_simt_kernel(const GemmArgs g) {
         int ml, kl;
         if (a_kfast) { ml = tid >> 2; kl = (tid & 3) * 4 + i; } else { kl = tid >> 4; ml = (tid & 15) * 4 + i; }
         const long m = m0 + ml, k = kk + kl;
-        As[kl][ml] = (m < m_end && k < k_end) ? ld<TA>(Ap, m * g.a_ms + k * g.a_ks) : 0.f;
+        float v = 0.f;
+        if (m < m_end && k < k_end) {
+          if (MODE == kRaggedM) {
+            const long row = g.a_rows ? (long)g.a_rows[m] : m;
+            v = ld<TA>(Ap, row * g.a_ms + k * g.a_ks);
+          } else {
+            const long row = g.a_rows ? (long)g.a_rows[k] : k;
+            v = ld<TA>(Ap, m * g.a_ms + row * g.a_ks);
+            if (g.a_scale) v = Elem<TA>::round(v * g.a_scale[k]);   // same rounding point as the matrix-core path
+          }
+        }
+        As[kl][ml] = v;
       }
 #pragma unroll
       for (int p = 0; p < (DUAL ? 2 : 1); ++p) {
@@ -103,10 +115,12 @@ __global__ __launch_bounds__(256) void gemm_simt_kernel(const GemmArgs g) {
     }
   }
 
+  float dots[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const long m = m0 + ty * 4 + i;
     if (m >= m_end) continue;
+    const float rs = (EPI == kEpiDSwiglu) ? g.row_scale[m] : 1.f;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const long n = n0 + tx * 4 + j;
@@ -121,16 +135,30 @@ __global__ __launch_bounds__(256) void gemm_simt_kernel(const GemmArgs g) {
         }
       } else if (EPI == kEpiSwiglu) {
         const float a = acc[0][i][j], b = acc[DUAL ? 1 : 0][i][j];
-        Elem<TB>::store(reinterpret_cast<TB*>(g.C[0]) + ci, a);
-        Elem<TB>::store(reinterpret_cast<TB*>(g.C[1]) + ci, b);
+        reinterpret_cast<float*>(g.C[0])[ci] = a;
+        reinterpret_cast<float*>(g.C[1])[ci] = b;
         Elem<TB>::store(reinterpret_cast<TB*>(g.C[2]) + ci, a * sigmoidf_(a) * b);
       } else {
-        const float dh = acc[0][i][j];
-        const float a = ld<TB>(g.E[0], ci), b = ld<TB>(g.E[1], ci);
+        const float u = acc[0][i][j];
+        const float a = reinterpret_cast<const float*>(g.E[0])[ci], b = reinterpret_cast<const float*>(g.E[1])[ci];
         const float sg = sigmoidf_(a);
+        dots[i] = fmaf(u, a * sg * b, dots[i]);
+        const float dh = rs * u;
         Elem<TB>::store(reinterpret_cast<TB*>(g.C[0]) + ci, dh * b * sg * (1.f + a * (1.f - sg)));
         Elem<TB>::store(reinterpret_cast<TB*>(g.C[1]) + ci, dh * a * sg);
       }
+    }
+  }
+  if (EPI == kEpiDSwiglu) {
+    // gate-gradient partial of this column tile: fixed-order sum over the 16 column threads of each row
+#pragma unroll
+    for (int i = 0; i < 4; ++i) Red[ty * 4 + i][tx] = dots[i];
+    __syncthreads();
+    if (tid < BM && m0 + tid < m_end) {
+      float sum = 0.f;
+#pragma unroll
+      for (int c = 0; c < 16; ++c) sum += Red[tid][c];
+      g.rowdot[(long)blockIdx.x * g.rowdot_stride + m0 + tid] = sum;
     }
   }
 }
@@ -161,8 +189,9 @@ int dispatch(int mode, int epi, const GemmArgs& g, hipStream_t s) {
 
 }  // namespace
 
-// Row tile of the ragged-M table this kernel expects.
+// Row tile of the ragged-M table this kernel expects, and its column tile.
 int simt_row_tile() { return BM; }
+int simt_col_tile() { return BN; }
 
 int launch_gemm_simt(int dtype_a, int dtype_b, int mode, int epi, const GemmArgs& g, hipStream_t s) {
   if (dtype_a == SPES_F32 && dtype_b == SPES_F32) return dispatch<float, float>(mode, epi, g, s);

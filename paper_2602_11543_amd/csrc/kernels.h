@@ -9,21 +9,22 @@ namespace spes {
 int routing_blocks(int R);
 int launch_topk_gate(float* logits, const float* bias, int T, int M, int k, int renorm, int* idx, float* gate, int* idx_copy,
                      float* gate_copy, float* lse, hipStream_t s);
-int launch_routing_tables(const int* idx, int R, int M, int* block_counts, int* expert_count, int* offset, int* perm,
-                          int* inv, int bm0, int* tab0, int bm1, int* tab1, int max_tiles, hipStream_t s);
-int launch_gating_bwd(const float* logits, const float* lse, const int* idx, const float* gate, const float* dgate, int T, int M,
-                      int k, int renorm, float* dlogits, hipStream_t s);
+int launch_routing_tables(const int* idx, const float* gate, int R, int M, int k, int* block_counts, int* expert_count,
+                          int* offset, int* perm, int* inv, int* row_token, float* row_gate, int bm0, int* tab0, int bm1,
+                          int* tab1, int max_tiles, hipStream_t s);
+int launch_gating_bwd(const float* logits, const float* lse, const int* idx, const float* gate, const float* dgate_part,
+                      int n_part, long part_stride, const int* inv, float* dgate, int T, int M, int k, int renorm, float* dlogits,
+                      hipStream_t s);
 
 // movement.hip (dtype = spes_dtype of the storage type)
-int launch_permute(int dtype, const void* x, const int* perm, int k, void* xp, long R, int d, hipStream_t s);
+int launch_permute(int dtype, const void* x, const int* row_token, void* xp, long R, int d, hipStream_t s);
 int launch_combine(int dtype, const void* yp, const int* inv, const float* gate, void* y, int T, int d, int k, hipStream_t s);
-int launch_dy_scatter(int dtype, const void* dy, const void* yp, const int* inv, const float* gate, void* dyp, float* dgate,
-                      int T, int d, int k, hipStream_t s);
 int launch_dx_gather(int dtype, const void* dxp, const int* inv, const float* dlogits, const void* w_router, void* dx, int T,
                      int d, int k, int M, hipStream_t s);
 
 // gemm_simt.hip
 int simt_row_tile();
+int simt_col_tile();
 
 // merge.hip
 struct MergeSrc;

@@ -7,16 +7,16 @@
 namespace spes {
 namespace {
 
-// xp[r,:] = x[perm[r] / k, :]
+// xp[r,:] = x[row_token[r], :]
 template <typename T>
-__global__ __launch_bounds__(256) void permute_kernel(const T* __restrict__ x, const int* __restrict__ perm, int k,
+__global__ __launch_bounds__(256) void permute_kernel(const T* __restrict__ x, const int* __restrict__ row_token,
                                                       T* __restrict__ xp, long total_vec, int nvec, int d) {
   constexpr int N = Vec16<T>::N;
   const long stride = (long)gridDim.x * 256;
   for (long v = (long)blockIdx.x * 256 + threadIdx.x; v < total_vec; v += stride) {
     const long r = v / nvec;
     const int c = (int)(v - r * nvec);
-    const int t = perm[r] / k;
+    const int t = row_token[r];
     Vec16<T> q;
     q.load(x + (long)t * d + c * N);
     q.store(xp + r * d + c * N);
@@ -49,36 +49,6 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ yp, 
     Vec16<T> o;
     o.pack(acc);
     o.store(y + t * d + c * N);
-  }
-}
-
-// dyp[r,:] = gate[t,j] * dy[t,:] and dgate[t,j] = <dy[t,:], yp[r,:]>, r = inv[t*k+j]; one block per token
-template <typename T>
-__global__ __launch_bounds__(256) void dy_scatter_kernel(const T* __restrict__ dy, const T* __restrict__ yp,
-                                                         const int* __restrict__ inv, const float* __restrict__ gate,
-                                                         T* __restrict__ dyp, float* __restrict__ dgate, int d, int k) {
-  constexpr int N = Vec16<T>::N;
-  __shared__ float red[4];
-  const long t = blockIdx.x;
-  const int nvec = d / N;
-  for (int j = 0; j < k; ++j) {
-    const long r = inv[t * k + j];
-    const float g = gate[t * k + j];
-    float part = 0.f;
-    for (int c = threadIdx.x; c < nvec; c += 256) {
-      Vec16<T> a, b, o;
-      a.load(dy + t * d + c * N);
-      b.load(yp + r * d + c * N);
-      float fa[N], fb[N], fo[N];
-      a.unpack(fa);
-      b.unpack(fb);
-#pragma unroll
-      for (int i = 0; i < N; ++i) { fo[i] = g * fa[i]; part = fmaf(fa[i], fb[i], part); }
-      o.pack(fo);
-      o.store(dyp + r * d + c * N);
-    }
-    const float tot = block_sum_256(part, red);
-    if (threadIdx.x == 0) dgate[t * k + j] = tot;
   }
 }
 
@@ -133,15 +103,15 @@ inline int ok() { return hipGetLastError() == hipSuccess ? SPES_OK : SPES_EHIP; 
 
 }  // namespace
 
-int launch_permute(int dtype, const void* x, const int* perm, int k, void* xp, long R, int d, hipStream_t s) {
+int launch_permute(int dtype, const void* x, const int* row_token, void* xp, long R, int d, hipStream_t s) {
   if (R == 0) return SPES_OK;
   if (dtype == SPES_F32) {
     const int nvec = d / 4;
-    hipLaunchKernelGGL(permute_kernel<float>, dim3(flat_grid(R * nvec)), dim3(256), 0, s, (const float*)x, perm, k, (float*)xp,
+    hipLaunchKernelGGL(permute_kernel<float>, dim3(flat_grid(R * nvec)), dim3(256), 0, s, (const float*)x, row_token, (float*)xp,
                        R * nvec, nvec, d);
   } else {
     const int nvec = d / 8;
-    hipLaunchKernelGGL(permute_kernel<bf16_t>, dim3(flat_grid(R * nvec)), dim3(256), 0, s, (const bf16_t*)x, perm, k,
+    hipLaunchKernelGGL(permute_kernel<bf16_t>, dim3(flat_grid(R * nvec)), dim3(256), 0, s, (const bf16_t*)x, row_token,
                        (bf16_t*)xp, R * nvec, nvec, d);
   }
   return ok();
@@ -157,17 +127,6 @@ int launch_combine(int dtype, const void* yp, const int* inv, const float* gate,
     hipLaunchKernelGGL(combine_kernel<bf16_t>, dim3(flat_grid((long)T * nvec)), dim3(256), 0, s, (const bf16_t*)yp, inv, gate,
                        (bf16_t*)y, (long)T * nvec, nvec, d, k);
   }
-  return ok();
-}
-
-int launch_dy_scatter(int dtype, const void* dy, const void* yp, const int* inv, const float* gate, void* dyp, float* dgate,
-                      int T, int d, int k, hipStream_t s) {
-  if (dtype == SPES_F32)
-    hipLaunchKernelGGL(dy_scatter_kernel<float>, dim3(T), dim3(256), 0, s, (const float*)dy, (const float*)yp, inv, gate,
-                       (float*)dyp, dgate, d, k);
-  else
-    hipLaunchKernelGGL(dy_scatter_kernel<bf16_t>, dim3(T), dim3(256), 0, s, (const bf16_t*)dy, (const bf16_t*)yp, inv, gate,
-                       (bf16_t*)dyp, dgate, d, k);
   return ok();
 }
 

@@ -109,8 +109,10 @@ __global__ __launch_bounds__(64) void scan_kernel(int* __restrict__ block_counts
   }
 }
 
-__global__ __launch_bounds__(256) void scatter_kernel(const int* __restrict__ idx, int R, const int* __restrict__ block_base,
-                                                      int* __restrict__ perm, int* __restrict__ inv) {
+__global__ __launch_bounds__(256) void scatter_kernel(const int* __restrict__ idx, const float* __restrict__ gate, int R, int k,
+                                                      const int* __restrict__ block_base, int* __restrict__ perm,
+                                                      int* __restrict__ inv, int* __restrict__ row_token,
+                                                      float* __restrict__ row_gate) {
   __shared__ int running[kMaxExperts];
   __shared__ int wcnt[4][kMaxExperts];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -141,6 +143,8 @@ __global__ __launch_bounds__(256) void scatter_kernel(const int* __restrict__ id
       for (int ww = 0; ww < w; ++ww) r += wcnt[ww][e];
       perm[r] = (int)flat;
       inv[flat] = r;
+      row_token[r] = (int)(flat / k);      // the same tables in expert-contiguous order, for the GEMM gathers
+      row_gate[r] = gate[flat];
     }
     __syncthreads();
     if (tid < kMaxExperts) {
@@ -156,14 +160,21 @@ __global__ __launch_bounds__(256) void scatter_kernel(const int* __restrict__ id
 // selected scores alone.
 __global__ __launch_bounds__(256) void gating_bwd_kernel(const float* __restrict__ logits, const float* __restrict__ lse,
                                                          const int* __restrict__ topk_idx, const float* __restrict__ topk_gate,
-                                                         const float* __restrict__ dgate, int T, int M, int k, int renorm,
-                                                         float* __restrict__ dlogits) {
+                                                         const float* __restrict__ dgate_part, int n_part, long part_stride,
+                                                         const int* __restrict__ inv, float* __restrict__ dgate, int T, int M,
+                                                         int k, int renorm, float* __restrict__ dlogits) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= T) return;
   // lane j < k holds selected pair j
   int sel = -1; float g = 0.f, dg = 0.f;
-  if (lane < k) { sel = topk_idx[(long)t * k + lane]; g = topk_gate[(long)t * k + lane]; dg = dgate[(long)t * k + lane]; }
+  if (lane < k) {
+    sel = topk_idx[(long)t * k + lane];
+    g = topk_gate[(long)t * k + lane];
+    const long r = inv[(long)t * k + lane];
+    for (int p = 0; p < n_part; ++p) dg += dgate_part[p * part_stride + r];   // column-tile partials, fixed order
+    dgate[(long)t * k + lane] = dg;
+  }
   float out = 0.f;
   if (renorm) {
     const float dot = wave_sum(g * dg);
@@ -199,19 +210,22 @@ int launch_topk_gate(float* logits, const float* bias, int T, int M, int k, int 
   return hipGetLastError() == hipSuccess ? SPES_OK : SPES_EHIP;
 }
 
-int launch_routing_tables(const int* idx, int R, int M, int* block_counts, int* expert_count, int* offset, int* perm,
-                          int* inv, int bm0, int* tab0, int bm1, int* tab1, int max_tiles, hipStream_t s) {
+int launch_routing_tables(const int* idx, const float* gate, int R, int M, int k, int* block_counts, int* expert_count,
+                          int* offset, int* perm, int* inv, int* row_token, float* row_gate, int bm0, int* tab0, int bm1,
+                          int* tab1, int max_tiles, hipStream_t s) {
   const int nblk = routing_blocks(R);
   hipLaunchKernelGGL(count_kernel, dim3(nblk), dim3(256), 0, s, idx, R, block_counts);
   hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(64), 0, s, block_counts, nblk, M, expert_count, offset, bm0, tab0, bm1, tab1,
                      max_tiles);
-  hipLaunchKernelGGL(scatter_kernel, dim3(nblk), dim3(256), 0, s, idx, R, block_counts, perm, inv);
+  hipLaunchKernelGGL(scatter_kernel, dim3(nblk), dim3(256), 0, s, idx, gate, R, k, block_counts, perm, inv, row_token, row_gate);
   return hipGetLastError() == hipSuccess ? SPES_OK : SPES_EHIP;
 }
 
-int launch_gating_bwd(const float* logits, const float* lse, const int* idx, const float* gate, const float* dgate, int T, int M,
-                      int k, int renorm, float* dlogits, hipStream_t s) {
-  hipLaunchKernelGGL(gating_bwd_kernel, dim3(cdiv(T, 4)), dim3(256), 0, s, logits, lse, idx, gate, dgate, T, M, k, renorm, dlogits);
+int launch_gating_bwd(const float* logits, const float* lse, const int* idx, const float* gate, const float* dgate_part,
+                      int n_part, long part_stride, const int* inv, float* dgate, int T, int M, int k, int renorm, float* dlogits,
+                      hipStream_t s) {
+  hipLaunchKernelGGL(gating_bwd_kernel, dim3(cdiv(T, 4)), dim3(256), 0, s, logits, lse, idx, gate, dgate_part, n_part, part_stride,
+                     inv, dgate, T, M, k, renorm, dlogits);
   return hipGetLastError() == hipSuccess ? SPES_OK : SPES_EHIP;
 }
 
