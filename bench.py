@@ -1,0 +1,167 @@
+#!/usr/bin/env python3
+"""Benchmark of the SPES MoE-layer hot path on one MI355X.
+
+One step = one forward plus one backward of the routed SwiGLU layer (every stage
+of the hot path: router GEMM, softmax/top-k, histogram/scan/rank, permute, grouped
+expert GEMMs, combine; backward with weight gradients for the trainable experts
+only) over one batch of seeded synthetic tokens already resident in HBM.
+
+Prints one JSON line: layer tokens/s, the roofline position of the dominant kernel
+(measured with HIP events recorded between stages on the launch stream), per-stage
+figures, and the fp64 CPU oracle timed on a bounded token sample as a baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
+PEAK_FP32_TFLOPS = 157.3      # fp32 vector/matrix peak (fp32 storage mode)
+PEAK_HBM_GBS = 8000.0         # HBM3E
+
+
+def stage_model(cfg, rho_rows):
+    """Algorithmic work of every stage: (bound, amount) with amount in FLOP (mfma/alu) or bytes (hbm)."""
+    T, d, M, f, k = cfg.T, cfg.d, cfg.M, cfg.f, cfg.k
+    R = T * k
+    s = 4 if cfg.dtype == "f32" else 2
+    mm = "alu" if cfg.dtype == "f32" else "mfma"
+    return {
+        "router_gemm": ("hbm", T * d * s + M * d * s + T * M * 4),
+        "softmax_topk": ("hbm", T * M * 4 + 2 * R * 4 * 2 + T * 4),
+        "hist_scan_rank": ("hbm", R * 4 * 7),
+        "permute": ("hbm", T * d * s + R * d * s),
+        "gemm_gate_up_swiglu": (mm, 4.0 * R * d * f),
+        "gemm_down": (mm, 2.0 * R * d * f),
+        "combine": ("hbm", R * d * s + T * d * s + R * 8),
+        "gemm_dgrad_down_dswiglu": (mm, 2.0 * R * d * f),
+        "gating_bwd": ("hbm", T * M * 4 * 2 + R * 4 * 4),
+        "gemm_dgrad_gate_up": (mm, 4.0 * R * d * f),
+        "wgrad_down": (mm, 2.0 * rho_rows * d * f),
+        "wgrad_gate": (mm, 2.0 * rho_rows * d * f),
+        "wgrad_up": (mm, 2.0 * rho_rows * d * f),
+        "router_wgrad": ("hbm", T * d * s + T * M * 4 + M * d * 4),
+        "unpermute_sum_router_dgrad": ("hbm", R * d * s + T * d * s + R * 4),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="cfg2", help="workload name from spes_workloads.CONFIGS")
+    ap.add_argument("--cpu-sample", type=int, default=1024, help="tokens of the workload timed through the fp64 oracle (0: skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2602_11543_amd as S
+    from spes_workloads import CONFIGS, layer_inputs
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from harness import DeviceLayer
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    cfg = CONFIGS[args.config]
+    t0 = time.time()
+    inp = layer_inputs(cfg)
+    L = DeviceLayer(inp, dev)
+    gen_s = time.time() - t0
+
+    def step():
+        L.fwd()
+        L.bwd(0)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    tokens_per_s = cfg.T / (ms_per_step * 1e-3)
+
+    # per-stage durations: HIP events recorded by the library on the launch stream, averaged over the same number of steps
+    S.spes_profile_enable(True)
+    acc = {}
+    for _ in range(args.steps):
+        L.fwd()
+        f_st = S.spes_profile_read(0)
+        L.bwd(0)
+        b_st = S.spes_profile_read(1)
+        for n, ms in f_st + b_st:
+            acc[n] = acc.get(n, 0.0) + ms
+    S.spes_profile_enable(False)
+    stage_ms = {n: v / args.steps for n, v in acc.items()}
+
+    count = L.count.cpu().numpy()
+    rows_trainable = int(count[np.nonzero(L.mask)[0]].sum())
+    model = stage_model(cfg, rows_trainable)
+    stages = {}
+    for n, ms in stage_ms.items():
+        bound, amount = model[n]
+        if bound == "hbm":
+            ach, peak, unit = amount / (ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
+        else:
+            ach, unit = amount / (ms * 1e-3) / 1e12, "TFLOP/s"
+            peak = PEAK_BF16_TFLOPS if bound == "mfma" else PEAK_FP32_TFLOPS
+        stages[n] = dict(ms=round(ms, 4), bound=bound, achieved=round(ach, 2), peak=peak, unit=unit, frac=round(ach / peak, 4))
+    dominant = max(stage_ms, key=stage_ms.get)
+    dom = stages[dominant]
+    gemm_names = [n for n, (b, _) in model.items() if b in ("mfma", "alu") and n in stage_ms]
+    gemm_flop = sum(model[n][1] for n in gemm_names)
+    gemm_ms = sum(stage_ms[n] for n in gemm_names)
+    gemm_peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS
+
+    out = {
+        "metric": "MoE layer fwd+bwd tokens/sec on 1 MI355X; grouped-GEMM MFMA util %",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: T={cfg.T} d_model={cfg.d} experts={cfg.M} d_ff={cfg.f} top_k={cfg.k} "
+                               f"renorm={cfg.renorm} trainable={cfg.n_trainable}/{cfg.M} ({cfg.dtype}, fp32 accumulate)",
+                   "trainable_row_fraction": round(rows_trainable / (cfg.T * cfg.k), 4),
+                   "max_over_mean_expert_load": round(float(count.max() / count.mean()), 2),
+                   "input_generation_s": round(gen_s, 1)},
+        "roofline": {"kernel": dominant, "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
+                     "unit": dom["unit"], "frac": dom["frac"], "traffic": None},
+        "grouped_gemm_util": {"flop": gemm_flop, "ms": round(gemm_ms, 4), "achieved_tflops": round(gemm_flop / (gemm_ms * 1e-3) / 1e12, 2),
+                              "peak_tflops": gemm_peak, "frac": round(gemm_flop / (gemm_ms * 1e-3) / 1e12 / gemm_peak, 4)},
+        "stages": stages,
+    }
+
+    if args.cpu_sample > 0:
+        from oracle import spes_oracle as O
+        n = min(args.cpu_sample, cfg.T)
+        xs, dys = inp["x"][:n], inp["dy"][:n]
+        t0 = time.perf_counter()
+        fwd = O.moe_forward(xs, inp["w_router"], inp["router_bias"], inp["w_gate"], inp["w_up"], inp["w_down"], cfg.k, cfg.renorm)
+        O.moe_backward(fwd, dys, xs, inp["w_router"], inp["w_gate"], inp["w_up"], inp["w_down"], cfg.renorm,
+                       wgrad_experts=L.trainable)
+        cpu_s = time.perf_counter() - t0
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count()
+        out["cpu_baseline"] = {"value": round(n / cpu_s, 1), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+                               "sample": f"fwd+bwd of the first {n} tokens of the workload through the fp64 numpy oracle "
+                                         f"(all {cfg.M} experts' weights, weight grads for the trainable ones), {cpu_s:.1f} s"}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

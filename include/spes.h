@@ -170,6 +170,18 @@ SPES_API int spes_expert_warmup_merge(int32_t n_experts, int32_t dtype, int32_t 
                                       const int64_t* elems, float* sim, int32_t* nbr,
                                       void* scratch, void* stream);
 
+/* Stage timing for benchmarks.  While enabled, spes_moe_fwd / spes_moe_bwd record a
+ * HIP event on the caller's stream after each of their stages (the steps of the hot
+ * path: router GEMM, softmax/top-k, histogram/scan/rank, permute, the grouped GEMMs,
+ * combine, ...).  spes_profile_read waits for the last recorded event of the most
+ * recent forward (which=0) or backward (which=1) and returns the number of stages,
+ * filling ms[i] (milliseconds) and names[i] (static strings; names may be NULL) for
+ * at most cap stages.  The events are the library's only process-wide state; calls
+ * that overlap on several streams while timing is enabled overwrite each other's
+ * records.  Not meant for production paths. */
+SPES_API int spes_profile_enable(int32_t on);
+SPES_API int spes_profile_read(int32_t which, float* ms, const char** names, int32_t cap);
+
 SPES_API const char* spes_strerror(int code);
 
 #ifdef __cplusplus

@@ -55,6 +55,10 @@ def _load() -> ctypes.CDLL:
     lib.spes_warmup_scratch_bytes.argtypes = [i32, i64]
     lib.spes_expert_warmup_merge.restype = i32
     lib.spes_expert_warmup_merge.argtypes = [i32, i32, i32, ctypes.c_float, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.spes_profile_enable.restype = i32
+    lib.spes_profile_enable.argtypes = [i32]
+    lib.spes_profile_read.restype = i32
+    lib.spes_profile_read.argtypes = [i32, vp, vp, i32]
     lib.spes_strerror.restype = ctypes.c_char_p
     lib.spes_strerror.argtypes = [i32]
     return lib
@@ -153,6 +157,21 @@ def spes_expert_warmup_merge(n_experts, dtype, top_K, alpha, w_in, elems_in, src
                                          ctypes.cast(sp, ctypes.c_void_p), ctypes.cast(dp, ctypes.c_void_p),
                                          el.ctypes.data_as(ctypes.c_void_p), _dev(sim), _dev(nbr), _dev(scratch),
                                          _stream(stream)), "spes_expert_warmup_merge")
+
+
+def spes_profile_enable(on: bool) -> None:
+    _check(_lib.spes_profile_enable(1 if on else 0), "spes_profile_enable")
+
+
+def spes_profile_read(which: int) -> list:
+    """[(stage name, milliseconds)] of the latest forward (0) or backward (1) while stage timing is enabled."""
+    cap = 24
+    ms = (ctypes.c_float * cap)()
+    names = (ctypes.c_char_p * cap)()
+    n = _lib.spes_profile_read(which, ctypes.cast(ms, ctypes.c_void_p), ctypes.cast(names, ctypes.c_void_p), cap)
+    if n < 0:
+        _check(n, "spes_profile_read")
+    return [(names[i].decode(), float(ms[i])) for i in range(n)]
 
 
 def ctx_view(shape: spes_moe_shape, ctx: torch.Tensor, name: str) -> torch.Tensor:

@@ -86,6 +86,28 @@ GemmArgs blank() {
   return g;
 }
 
+// Optional stage timing: HIP events recorded on the caller's stream between the stages of fwd and bwd.
+// This is the library's only process-level state; it holds no device memory.
+constexpr int kMaxStages = 24;
+struct Profile {
+  bool on = false, created = false;
+  hipEvent_t ev[2][kMaxStages + 1];
+  const char* name[2][kMaxStages];
+  int n[2] = {0, 0};
+} g_prof;
+
+void prof_begin(int which, hipStream_t s) {
+  if (!g_prof.on) return;
+  g_prof.n[which] = 0;
+  (void)hipEventRecord(g_prof.ev[which][0], s);
+}
+void prof_mark(int which, const char* name, hipStream_t s) {
+  if (!g_prof.on || g_prof.n[which] >= kMaxStages) return;
+  const int i = g_prof.n[which]++;
+  g_prof.name[which][i] = name;
+  (void)hipEventRecord(g_prof.ev[which][i + 1], s);
+}
+
 #define SPES_TRY(expr) do { int rc_ = (expr); if (rc_ != SPES_OK) return rc_; } while (0)
 
 }  // namespace
@@ -119,6 +141,7 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
   const int T = shape->T, d = shape->d_model, M = shape->n_experts, f = shape->d_ff, k = shape->top_k, dt = shape->dtype;
   const long R = (long)T * k;
 
+  prof_begin(0, s);
   // router scores: logits[T,M] = x W_r^T
   {
     GemmArgs g = blank();
@@ -128,13 +151,17 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
     g.C[0] = at<float>(ctx, L.pub.logits); g.c_ms = M; g.c_f32 = 1;
     SPES_TRY(launch_gemm_simt(dt, dt, kGroupedK, kEpiStore, g, s));
   }
+  prof_mark(0, "router_gemm", s);
   SPES_TRY(launch_topk_gate(at<float>(ctx, L.pub.logits), router_bias, T, M, k, shape->renorm_topk, topk_idx, topk_gate,
                             at<int>(ctx, L.pub.topk_idx), at<float>(ctx, L.pub.topk_gate), at<float>(ctx, L.pub.lse), s));
+  prof_mark(0, "softmax_topk", s);
   SPES_TRY(launch_routing_tables(topk_idx, topk_gate, (int)R, M, k, at<int>(ctx, L.block_counts), expert_count,
                                  at<int>(ctx, L.pub.offset), at<int>(ctx, L.pub.perm), at<int>(ctx, L.pub.inv),
                                  at<int>(ctx, L.row_token), at<float>(ctx, L.row_gate), simt_row_tile(),
                                  at<int>(ctx, L.tab_simt), 0, at<int>(ctx, L.tab_mfma), L.max_tiles, s));
+  prof_mark(0, "hist_scan_rank", s);
   SPES_TRY(launch_permute(dt, x, at<int>(ctx, L.row_token), at<void>(ctx, L.pub.xp), R, d, s));
+  prof_mark(0, "permute", s);
   // a = xp W_g^T, b = xp W_u^T, h = SiLU(a) * b
   {
     GemmArgs g = blank();
@@ -145,6 +172,7 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
     ragged_tables(g, ctx, L);
     SPES_TRY(launch_gemm_simt(dt, dt, kRaggedM, kEpiSwiglu, g, s));
   }
+  prof_mark(0, "gemm_gate_up_swiglu", s);
   // yp = h W_d^T
   {
     GemmArgs g = blank();
@@ -155,7 +183,9 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
     ragged_tables(g, ctx, L);
     SPES_TRY(launch_gemm_simt(dt, dt, kRaggedM, kEpiStore, g, s));
   }
+  prof_mark(0, "gemm_down", s);
   SPES_TRY(launch_combine(dt, at<void>(ctx, L.pub.yp), at<int>(ctx, L.pub.inv), topk_gate, y, T, d, k, s));
+  prof_mark(0, "combine", s);
   return SPES_OK;
 }
 
@@ -185,6 +215,7 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
   // through the SwiGLU, da and db of the gate-scaled upstream gradient
   const long R = (long)T * k;
   const int n_part = cdiv(f, simt_col_tile());
+  prof_begin(1, s);
   {
     GemmArgs g = blank();
     g.A[0] = dy; g.a_ms = d; g.a_ks = 1; g.a_rows = at<int>(ctx, L.row_token);
@@ -197,9 +228,11 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
     ragged_tables(g, ctx, L);
     SPES_TRY(launch_gemm_simt(dt, dt, kRaggedM, kEpiDSwiglu, g, s));
   }
+  prof_mark(1, "gemm_dgrad_down_dswiglu", s);
   SPES_TRY(launch_gating_bwd(at<float>(ctx, L.pub.logits), at<float>(ctx, L.pub.lse), idx, gate, at<float>(ctx, L.dgate_part),
                              n_part, R, inv, at<float>(ctx, L.pub.dgate), T, M, k, shape->renorm_topk,
                              at<float>(ctx, L.pub.dlogits), s));
+  prof_mark(1, "gating_bwd", s);
   // dxp = da W_g + db W_u
   {
     GemmArgs g = blank();
@@ -211,6 +244,7 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
     ragged_tables(g, ctx, L);
     SPES_TRY(launch_gemm_simt(dt, dt, kRaggedM, kEpiStore, g, s));
   }
+  prof_mark(1, "gemm_dgrad_gate_up", s);
   // weight gradients of the trainable experts only, into their compact slots
   if (n_train > 0) {
     GemmArgs g = blank();
@@ -223,13 +257,16 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
     g.B[0] = at<void>(ctx, L.pub.h); g.b_ns = 1; g.b_ks = f;
     g.Mdim = d; g.Ndim = f; g.C[0] = d_w_down; g.c_ms = f; g.c_gs = (long)d * f;
     SPES_TRY(launch_gemm_simt(dt, dt, kGroupedK, kEpiStore, g, s));
+    prof_mark(1, "wgrad_down", s);
     // dW_g[f,d] = da^T xp ; dW_u[f,d] = db^T xp
     g.B[0] = at<void>(ctx, L.pub.xp); g.b_ns = 1; g.b_ks = d;
     g.a_ms = 1; g.a_ks = f; g.a_rows = nullptr; g.a_scale = nullptr; g.Mdim = f; g.Ndim = d; g.c_ms = d; g.c_gs = (long)f * d;
     g.A[0] = at<void>(ctx, L.da); g.C[0] = d_w_gate;
     SPES_TRY(launch_gemm_simt(dt, dt, kGroupedK, kEpiStore, g, s));
+    prof_mark(1, "wgrad_gate", s);
     g.A[0] = at<void>(ctx, L.db); g.C[0] = d_w_up;
     SPES_TRY(launch_gemm_simt(dt, dt, kGroupedK, kEpiStore, g, s));
+    prof_mark(1, "wgrad_up", s);
   }
   // dW_r[M,d] = dlogits^T x
   {
@@ -240,8 +277,10 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
     g.C[0] = d_w_router; g.c_ms = d; g.c_f32 = 1; g.accumulate = accumulate;
     SPES_TRY(launch_gemm_simt(SPES_F32, dt, kGroupedK, kEpiStore, g, s));
   }
+  prof_mark(1, "router_wgrad", s);
   // dx = unpermuted sum of dxp + dlogits W_r
   SPES_TRY(launch_dx_gather(dt, at<void>(ctx, L.dxp), inv, at<float>(ctx, L.pub.dlogits), w_router, dx, T, d, k, M, s));
+  prof_mark(1, "unpermute_sum_router_dgrad", s);
   return SPES_OK;
 }
 
@@ -312,6 +351,30 @@ SPES_API int spes_expert_warmup_merge(int32_t n_experts, int32_t dtype, int32_t 
   for (int m = 0; m < n_mats; ++m)
     SPES_TRY(launch_warmup_mix(dtype, M, elems[m], top_K, alpha, src[m], dst[m], nbr, s));
   return SPES_OK;
+}
+
+SPES_API int spes_profile_enable(int32_t on) {
+  if (on && !g_prof.created) {
+    for (int w = 0; w < 2; ++w)
+      for (int i = 0; i <= kMaxStages; ++i)
+        if (hipEventCreate(&g_prof.ev[w][i]) != hipSuccess) return SPES_EHIP;
+    g_prof.created = true;
+  }
+  g_prof.on = on != 0;
+  g_prof.n[0] = g_prof.n[1] = 0;
+  return SPES_OK;
+}
+
+SPES_API int spes_profile_read(int32_t which, float* ms, const char** names, int32_t cap) {
+  if ((which != 0 && which != 1) || !ms || cap <= 0 || !g_prof.created) return SPES_EINVAL;
+  const int n = g_prof.n[which] < cap ? g_prof.n[which] : cap;
+  if (n == 0) return 0;
+  if (hipEventSynchronize(g_prof.ev[which][g_prof.n[which]]) != hipSuccess) return SPES_EHIP;
+  for (int i = 0; i < n; ++i) {
+    if (hipEventElapsedTime(&ms[i], g_prof.ev[which][i], g_prof.ev[which][i + 1]) != hipSuccess) return SPES_EHIP;
+    if (names) names[i] = g_prof.name[which][i];
+  }
+  return n;
 }
 
 SPES_API const char* spes_strerror(int code) {
