@@ -8,10 +8,12 @@ using namespace spes;
 
 namespace {
 
+constexpr int kRouterSplit = 64;   // chunks of the token axis in the router weight gradient
+
 struct Layout {
   spes_moe_ctx_layout pub;
-  size_t block_counts, tab_simt, tab_mfma, row_token, row_gate, dgate_part, da, db, dxp;
-  int max_tiles, max_col_tiles;
+  size_t block_counts, tab_simt, tab_mfma, row_token, row_gate, dgate_part, da, db, hg, dxp, wr_part;
+  int max_tiles, max_tiles_mfma, max_col_tiles;
 };
 
 bool shape_ok(const spes_moe_shape* s) {
@@ -36,6 +38,7 @@ Layout make_layout(const spes_moe_shape* s) {
   const size_t T = s->T, d = s->d_model, M = s->n_experts, f = s->d_ff, k = s->top_k;
   const size_t R = T * k, es = s->dtype == SPES_F32 ? 4 : 2;
   L.max_tiles = (int)(R / 64 + M + 1);
+  L.max_tiles_mfma = (int)(R / 256 + M + 1);
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += round_up(bytes, 256); return o; };
   L.pub.logits = take(T * M * 4);
@@ -57,11 +60,13 @@ Layout make_layout(const spes_moe_shape* s) {
   L.pub.yp = take(R * d * es);
   L.pub.dlogits = take(T * M * 4);
   L.pub.dgate = take(T * k * 4);
-  L.max_col_tiles = cdiv((long)f, 64);
+  L.max_col_tiles = cdiv((long)f, 64) > mfma_rowdot_parts((int)f) ? cdiv((long)f, 64) : mfma_rowdot_parts((int)f);
   L.dgate_part = take((size_t)L.max_col_tiles * R * 4);
   L.da = take(R * f * es);
   L.db = take(R * f * es);
+  L.hg = take(R * f * es);
   L.dxp = take(R * d * es);
+  L.wr_part = take((size_t)kRouterSplit * M * d * 4);
   L.pub.total = off;
   return L;
 }
@@ -69,13 +74,19 @@ Layout make_layout(const spes_moe_shape* s) {
 template <typename T>
 T* at(void* base, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(base) + off); }
 
-void ragged_tables(GemmArgs& g, void* ctx, const Layout& L) {
-  int* tab = at<int>(ctx, L.tab_simt);
+// bf16 storage runs the expert GEMMs on the matrix cores, fp32 storage on the vector ALUs
+int expert_gemm(int dt, int mode, int epi, bool a_kcontig, bool b_kcontig, const GemmArgs& g, hipStream_t s) {
+  if (dt == SPES_BF16) return launch_gemm_mfma(mode, epi, a_kcontig, b_kcontig, g, s);
+  return launch_gemm_simt(dt, dt, mode, epi, g, s);
+}
+
+void ragged_tables(GemmArgs& g, void* ctx, const Layout& L, int dt) {
+  int* tab = at<int>(ctx, dt == SPES_BF16 ? L.tab_mfma : L.tab_simt);
   g.n_tiles = tab;
   g.tile_expert = tab + 1;
   g.tile_row0 = tab + 1 + L.max_tiles;
   g.offset = at<int>(ctx, L.pub.offset);
-  g.max_tiles = L.max_tiles;
+  g.max_tiles = dt == SPES_BF16 ? L.max_tiles_mfma : L.max_tiles;   // launch bound on the number of row tiles
 }
 
 GemmArgs blank() {
@@ -149,7 +160,9 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
     g.B[0] = w_router; g.b_ns = d; g.b_ks = 1;
     g.Kdim = d; g.kchunk = d; g.Mdim = T; g.Ndim = M;
     g.C[0] = at<float>(ctx, L.pub.logits); g.c_ms = M; g.c_f32 = 1;
-    SPES_TRY(launch_gemm_simt(dt, dt, kGroupedK, kEpiStore, g, s));
+    // the matrix-core epilogue stores four columns at a time
+    if (dt == SPES_BF16 && M % 4 == 0) SPES_TRY(launch_gemm_mfma(kGroupedK, kEpiStore, true, true, g, s));
+    else SPES_TRY(launch_gemm_simt(dt, dt, kGroupedK, kEpiStore, g, s));
   }
   prof_mark(0, "router_gemm", s);
   SPES_TRY(launch_topk_gate(at<float>(ctx, L.pub.logits), router_bias, T, M, k, shape->renorm_topk, topk_idx, topk_gate,
@@ -158,7 +171,7 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
   SPES_TRY(launch_routing_tables(topk_idx, topk_gate, (int)R, M, k, at<int>(ctx, L.block_counts), expert_count,
                                  at<int>(ctx, L.pub.offset), at<int>(ctx, L.pub.perm), at<int>(ctx, L.pub.inv),
                                  at<int>(ctx, L.row_token), at<float>(ctx, L.row_gate), simt_row_tile(),
-                                 at<int>(ctx, L.tab_simt), 0, at<int>(ctx, L.tab_mfma), L.max_tiles, s));
+                                 at<int>(ctx, L.tab_simt), mfma_row_tile(), at<int>(ctx, L.tab_mfma), L.max_tiles, s));
   prof_mark(0, "hist_scan_rank", s);
   SPES_TRY(launch_permute(dt, x, at<int>(ctx, L.row_token), at<void>(ctx, L.pub.xp), R, d, s));
   prof_mark(0, "permute", s);
@@ -169,8 +182,8 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
     g.B[0] = w_gate; g.B[1] = w_up; g.b_ns = d; g.b_ks = 1; g.b_gs = (long)f * d;
     g.Kdim = d; g.Ndim = f;
     g.C[0] = at<void>(ctx, L.pub.a); g.C[1] = at<void>(ctx, L.pub.b); g.C[2] = at<void>(ctx, L.pub.h); g.c_ms = f;
-    ragged_tables(g, ctx, L);
-    SPES_TRY(launch_gemm_simt(dt, dt, kRaggedM, kEpiSwiglu, g, s));
+    ragged_tables(g, ctx, L, dt);
+    SPES_TRY(expert_gemm(dt, kRaggedM, kEpiSwiglu, true, true, g, s));
   }
   prof_mark(0, "gemm_gate_up_swiglu", s);
   // yp = h W_d^T
@@ -180,8 +193,8 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
     g.B[0] = w_down; g.b_ns = f; g.b_ks = 1; g.b_gs = (long)d * f;
     g.Kdim = f; g.Ndim = d;
     g.C[0] = at<void>(ctx, L.pub.yp); g.c_ms = d;
-    ragged_tables(g, ctx, L);
-    SPES_TRY(launch_gemm_simt(dt, dt, kRaggedM, kEpiStore, g, s));
+    ragged_tables(g, ctx, L, dt);
+    SPES_TRY(expert_gemm(dt, kRaggedM, kEpiStore, true, true, g, s));
   }
   prof_mark(0, "gemm_down", s);
   SPES_TRY(launch_combine(dt, at<void>(ctx, L.pub.yp), at<int>(ctx, L.pub.inv), topk_gate, y, T, d, k, s));
@@ -214,7 +227,7 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
   // u = dy[token] W_d per routed row; its epilogue yields the gate gradient <u, h> (per column tile) and,
   // through the SwiGLU, da and db of the gate-scaled upstream gradient
   const long R = (long)T * k;
-  const int n_part = cdiv(f, simt_col_tile());
+  const int n_part = dt == SPES_BF16 ? mfma_rowdot_parts(f) : cdiv(f, simt_col_tile());
   prof_begin(1, s);
   {
     GemmArgs g = blank();
@@ -222,11 +235,11 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
     g.B[0] = w_down; g.b_ns = 1; g.b_ks = f; g.b_gs = (long)d * f;
     g.Kdim = d; g.Ndim = f;
     g.E[0] = at<void>(ctx, L.pub.a); g.E[1] = at<void>(ctx, L.pub.b);
-    g.C[0] = at<void>(ctx, L.da); g.C[1] = at<void>(ctx, L.db); g.c_ms = f;
+    g.C[0] = at<void>(ctx, L.da); g.C[1] = at<void>(ctx, L.db); g.C[2] = at<void>(ctx, L.hg); g.c_ms = f;
     g.row_scale = at<float>(ctx, L.row_gate);
     g.rowdot = at<float>(ctx, L.dgate_part); g.rowdot_stride = R;
-    ragged_tables(g, ctx, L);
-    SPES_TRY(launch_gemm_simt(dt, dt, kRaggedM, kEpiDSwiglu, g, s));
+    ragged_tables(g, ctx, L, dt);
+    SPES_TRY(expert_gemm(dt, kRaggedM, kEpiDSwiglu, true, false, g, s));
   }
   prof_mark(1, "gemm_dgrad_down_dswiglu", s);
   SPES_TRY(launch_gating_bwd(at<float>(ctx, L.pub.logits), at<float>(ctx, L.pub.lse), idx, gate, at<float>(ctx, L.dgate_part),
@@ -241,8 +254,8 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
     g.B[0] = w_gate; g.B[1] = w_up; g.b_ns = 1; g.b_ks = d; g.b_gs = (long)f * d;
     g.Kdim = f; g.Ndim = d;
     g.C[0] = at<void>(ctx, L.dxp); g.c_ms = d;
-    ragged_tables(g, ctx, L);
-    SPES_TRY(launch_gemm_simt(dt, dt, kRaggedM, kEpiStore, g, s));
+    ragged_tables(g, ctx, L, dt);
+    SPES_TRY(expert_gemm(dt, kRaggedM, kEpiStore, true, false, g, s));
   }
   prof_mark(1, "gemm_dgrad_gate_up", s);
   // weight gradients of the trainable experts only, into their compact slots
@@ -252,20 +265,20 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
     memcpy(g.group_expert, train_list, n_train);
     g.offset = at<int>(ctx, L.pub.offset);
     g.c_f32 = 1; g.accumulate = accumulate;
-    // dW_d[d,f] = (gate * dy[token])^T h over the expert's rows
-    g.A[0] = dy; g.a_ms = 1; g.a_ks = d; g.a_rows = at<int>(ctx, L.row_token); g.a_scale = at<float>(ctx, L.row_gate);
-    g.B[0] = at<void>(ctx, L.pub.h); g.b_ns = 1; g.b_ks = f;
+    // dW_d[d,f] = dy[token]^T (gate * h) over the expert's rows
+    g.A[0] = dy; g.a_ms = 1; g.a_ks = d; g.a_rows = at<int>(ctx, L.row_token);
+    g.B[0] = at<void>(ctx, L.hg); g.b_ns = 1; g.b_ks = f;
     g.Mdim = d; g.Ndim = f; g.C[0] = d_w_down; g.c_ms = f; g.c_gs = (long)d * f;
-    SPES_TRY(launch_gemm_simt(dt, dt, kGroupedK, kEpiStore, g, s));
+    SPES_TRY(expert_gemm(dt, kGroupedK, kEpiStore, false, false, g, s));
     prof_mark(1, "wgrad_down", s);
     // dW_g[f,d] = da^T xp ; dW_u[f,d] = db^T xp
     g.B[0] = at<void>(ctx, L.pub.xp); g.b_ns = 1; g.b_ks = d;
-    g.a_ms = 1; g.a_ks = f; g.a_rows = nullptr; g.a_scale = nullptr; g.Mdim = f; g.Ndim = d; g.c_ms = d; g.c_gs = (long)f * d;
+    g.a_ms = 1; g.a_ks = f; g.a_rows = nullptr; g.Mdim = f; g.Ndim = d; g.c_ms = d; g.c_gs = (long)f * d;
     g.A[0] = at<void>(ctx, L.da); g.C[0] = d_w_gate;
-    SPES_TRY(launch_gemm_simt(dt, dt, kGroupedK, kEpiStore, g, s));
+    SPES_TRY(expert_gemm(dt, kGroupedK, kEpiStore, false, false, g, s));
     prof_mark(1, "wgrad_gate", s);
     g.A[0] = at<void>(ctx, L.db); g.C[0] = d_w_up;
-    SPES_TRY(launch_gemm_simt(dt, dt, kGroupedK, kEpiStore, g, s));
+    SPES_TRY(expert_gemm(dt, kGroupedK, kEpiStore, false, false, g, s));
     prof_mark(1, "wgrad_up", s);
   }
   // dW_r[M,d] = dlogits^T x
@@ -273,9 +286,11 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
     GemmArgs g = blank();
     g.A[0] = at<float>(ctx, L.pub.dlogits); g.a_ms = 1; g.a_ks = M;
     g.B[0] = x; g.b_ns = 1; g.b_ks = d;
-    g.Kdim = T; g.kchunk = T; g.Mdim = M; g.Ndim = d;
-    g.C[0] = d_w_router; g.c_ms = d; g.c_f32 = 1; g.accumulate = accumulate;
+    // the token axis is cut into chunks whose partial products are then added in a fixed order
+    g.Kdim = T; g.kchunk = cdiv(T, kRouterSplit); g.n_groups = cdiv(T, g.kchunk); g.Mdim = M; g.Ndim = d;
+    g.C[0] = at<float>(ctx, L.wr_part); g.c_ms = d; g.c_gs = (long)M * d; g.c_f32 = 1;
     SPES_TRY(launch_gemm_simt(SPES_F32, dt, kGroupedK, kEpiStore, g, s));
+    SPES_TRY(launch_reduce_partials(at<float>(ctx, L.wr_part), g.n_groups, (long)M * d, d_w_router, accumulate, s));
   }
   prof_mark(1, "router_wgrad", s);
   // dx = unpermuted sum of dxp + dlogits W_r

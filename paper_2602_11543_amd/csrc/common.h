@@ -103,6 +103,6 @@ __device__ __forceinline__ float block_sum_256(float v, float* smem4) {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
+__host__ __device__ inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
 
 }  // namespace spes

@@ -20,7 +20,7 @@ enum GemmEpi {
   kEpiSwiglu = 1,   // two accumulators a (pair 0), b (pair 1): C[0]=a (f32), C[1]=b (f32), C[2]=SiLU(a)*b
   kEpiDSwiglu = 2   // acc = u (row of dy times W_d); with saved a=E[0], b=E[1] (f32), h = SiLU(a)*b:
                     //   rowdot[tile_n][m] = sum_n u*h (the gate gradient), dh = row_scale[m]*u,
-                    //   C[0] = da = dh*b*s(1+a(1-s)), C[1] = db = dh*a*s, s = sigmoid(a)
+                    //   C[0] = da = dh*b*s(1+a(1-s)), C[1] = db = dh*a*s, s = sigmoid(a), C[2] = row_scale[m]*h
 };
 
 struct GemmArgs {
@@ -28,7 +28,6 @@ struct GemmArgs {
   const void* B[2];
   long a_ms, a_ks;        // element strides of A along m, k
   const int* a_rows;      // optional gather: kRaggedM reads row a_rows[m] in place of m; kGroupedK reads row a_rows[k] in place of k
-  const float* a_scale;   // optional (kGroupedK): A(m,k) is multiplied by a_scale[k]
   const float* row_scale; // kEpiDSwiglu: per-row factor (the gate of the routed pair)
   float* rowdot;          // kEpiDSwiglu: [gridDim.x, rowdot_stride] partial gate gradients
   long rowdot_stride;
@@ -58,5 +57,10 @@ __device__ __forceinline__ float sigmoidf_(float a) { return 1.0f / (1.0f + __ex
 
 // launchers (storage type T of A/B/C unless stated); defined in gemm_simt.hip / gemm_mfma.hip
 int launch_gemm_simt(int dtype_a, int dtype_b, int mode, int epi, const GemmArgs& g, hipStream_t s);
+int launch_gemm_mfma(int mode, int epi, bool a_kcontig, bool b_kcontig, const GemmArgs& g, hipStream_t s);
+int simt_row_tile();
+int simt_col_tile();
+int mfma_row_tile();
+int mfma_rowdot_parts(int ndim);
 
 }  // namespace spes

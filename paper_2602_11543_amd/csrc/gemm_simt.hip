@@ -78,7 +78,6 @@ __global__ __launch_bounds__(256) void gemm_simt_kernel(const GemmArgs g) {
           } else {
             const long row = g.a_rows ? (long)g.a_rows[k] : k;
             v = ld<TA>(Ap, m * g.a_ms + row * g.a_ks);
-            if (g.a_scale) v = Elem<TA>::round(v * g.a_scale[k]);   // same rounding point as the matrix-core path
           }
         }
         As[kl][ml] = v;
@@ -142,8 +141,10 @@ __global__ __launch_bounds__(256) void gemm_simt_kernel(const GemmArgs g) {
         const float u = acc[0][i][j];
         const float a = reinterpret_cast<const float*>(g.E[0])[ci], b = reinterpret_cast<const float*>(g.E[1])[ci];
         const float sg = sigmoidf_(a);
-        dots[i] = fmaf(u, a * sg * b, dots[i]);
+        const float h = a * sg * b;
+        dots[i] = fmaf(u, h, dots[i]);
         const float dh = rs * u;
+        Elem<TB>::store(reinterpret_cast<TB*>(g.C[2]) + ci, rs * h);
         Elem<TB>::store(reinterpret_cast<TB*>(g.C[0]) + ci, dh * b * sg * (1.f + a * (1.f - sg)));
         Elem<TB>::store(reinterpret_cast<TB*>(g.C[1]) + ci, dh * a * sg);
       }

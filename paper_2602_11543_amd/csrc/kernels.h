@@ -22,9 +22,8 @@ int launch_combine(int dtype, const void* yp, const int* inv, const float* gate,
 int launch_dx_gather(int dtype, const void* dxp, const int* inv, const float* dlogits, const void* w_router, void* dx, int T,
                      int d, int k, int M, hipStream_t s);
 
-// gemm_simt.hip
-int simt_row_tile();
-int simt_col_tile();
+// out[i] (+)= sum_p partial[p*n + i], p ascending (movement.hip)
+int launch_reduce_partials(const float* partial, int n_partial, long n, float* out, int accumulate, hipStream_t s);
 
 // merge.hip
 struct MergeSrc;

@@ -92,6 +92,20 @@ __global__ __launch_bounds__(256) void dx_gather_kernel(const T* __restrict__ dx
   }
 }
 
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int n_partial, long n,
+                                                              float* __restrict__ out, int accumulate) {
+  const long i = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i >= n) return;
+  float4 acc = accumulate ? *reinterpret_cast<const float4*>(out + i) : make_float4(0.f, 0.f, 0.f, 0.f);
+  float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int p = 0; p < n_partial; ++p) {
+    const float4 v = *reinterpret_cast<const float4*>(partial + (long)p * n + i);
+    sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+  }
+  acc.x += sum.x; acc.y += sum.y; acc.z += sum.z; acc.w += sum.w;
+  *reinterpret_cast<float4*>(out + i) = acc;
+}
+
 inline int flat_grid(long total_vec) {
   long b = (total_vec + 256L * 4 - 1) / (256L * 4);
   if (b < 1) b = 1;
@@ -127,6 +141,11 @@ int launch_combine(int dtype, const void* yp, const int* inv, const float* gate,
     hipLaunchKernelGGL(combine_kernel<bf16_t>, dim3(flat_grid((long)T * nvec)), dim3(256), 0, s, (const bf16_t*)yp, inv, gate,
                        (bf16_t*)y, (long)T * nvec, nvec, d, k);
   }
+  return ok();
+}
+
+int launch_reduce_partials(const float* partial, int n_partial, long n, float* out, int accumulate, hipStream_t s) {
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(n, 1024)), dim3(256), 0, s, partial, n_partial, n, out, accumulate);
   return ok();
 }
 
