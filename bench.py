@@ -57,7 +57,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="cfg2", help="workload name from spes_workloads.CONFIGS")
-    ap.add_argument("--cpu-sample", type=int, default=1024, help="tokens of the workload timed through the fp64 oracle (0: skip)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device-to-device copy (reference point for HBM byte counters)")
+    ap.add_argument("--cpu-sample", type=int, default=8192, help="tokens of the workload timed through the fp64 oracle (0: skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -82,6 +84,14 @@ def main() -> int:
     def step():
         L.fwd()
         L.bwd(0)
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
