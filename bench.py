@@ -51,12 +51,83 @@ def stage_model(cfg, rho_rows):
     }
 
 
+def bench_merge(args) -> int:
+    """Expert synchronisation sweep (16 node copies of a 64-expert layer, d=2048, f=1024, bf16) and warm-up merge."""
+    import numpy as np
+    import torch
+
+    import paper_2602_11543_amd as S
+
+    dev = torch.device("cuda:0")
+    M, d, f, nodes, per = 64, 2048, 1024, 16, 16
+    E = d * f
+    rng = np.random.default_rng(20260216)
+    slot = np.full((nodes, M), -1, dtype=np.int32)
+    for i in range(nodes):
+        sub = np.sort(rng.permutation(M)[:per])
+        slot[i, sub] = np.arange(per, dtype=np.int32)
+    w = (0.5 + rng.random(nodes)).astype(np.float32)
+    cnt = (slot >= 0).sum(0)
+    mats = []
+    for _ in range(3):   # gate, up, down projections: one call per parameter matrix
+        base = (torch.randn(M, E, device=dev) * 0.02).to(torch.bfloat16)
+        stores = [(torch.randn(per, E, device=dev) * 0.02).to(torch.bfloat16) for _ in range(nodes)]
+        mats.append((base, stores))
+    tc = torch.empty(M, dtype=torch.int32, device=dev)
+
+    def sync_step():
+        for base, stores in mats:
+            S.spes_expert_merge(M, E, S.SPES_BF16, stores, slot, w, base, tc)
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(steps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / steps
+
+    ms_sync = timed(sync_step, args.steps, args.warmup)
+    bytes_sync = 3 * 2 * E * (int(cnt.sum()) + int((cnt > 0).sum()))
+    # warm-up merge on the merged store: similarity on the gate projection, all three matrices mixed
+    K, alpha = 4, 0.1
+    srcs = [m[0] for m in mats]
+    dsts = [torch.empty_like(t) for t in srcs]
+    sim = torch.empty(M, M, dtype=torch.float32, device=dev)
+    nbr = torch.empty(M, K, dtype=torch.int32, device=dev)
+    scratch = torch.empty(S.spes_warmup_scratch_bytes(M, E), dtype=torch.uint8, device=dev)
+
+    def warm_step():
+        S.spes_expert_warmup_merge(M, S.SPES_BF16, K, alpha, srcs[0], E, srcs, dsts, [E, E, E], sim, nbr, scratch)
+
+    ms_warm = timed(warm_step, args.steps, args.warmup)
+    bytes_warm = 2 * M * E + 3 * 2 * M * E * (K + 1 + 1)      # Gram pass + (K+1) reads and one write per matrix
+    out = {"metric": "expert merge GB/s on 1 MI355X", "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"cfg5 merge: {nodes} nodes x {per} of {M} experts, d={d} f={f}, 3 matrices, weighted; "
+                                  f"trainers/expert min {int(cnt.min())} max {int(cnt.max())} sum {int(cnt.sum())}"},
+           "sync_merge": {"ms": round(ms_sync, 4), "bytes": bytes_sync, "achieved": round(bytes_sync / ms_sync / 1e6, 1),
+                          "peak": PEAK_HBM_GBS, "frac": round(bytes_sync / ms_sync / 1e6 / PEAK_HBM_GBS, 4), "bound": "hbm"},
+           "warmup_merge": {"ms": round(ms_warm, 4), "bytes": bytes_warm, "achieved": round(bytes_warm / ms_warm / 1e6, 1),
+                            "peak": PEAK_HBM_GBS, "frac": round(bytes_warm / ms_warm / 1e6 / PEAK_HBM_GBS, 4), "bound": "hbm",
+                            "K": K, "alpha": alpha}}
+    out["value"] = out["sync_merge"]["achieved"]
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="cfg2", help="workload name from spes_workloads.CONFIGS")
+    ap.add_argument("--workload", default="layer", choices=["layer", "merge"],
+                    help="layer: fwd+bwd of the MoE layer (the headline metric); merge: expert synchronisation sweep")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (reference point for HBM byte counters)")
     ap.add_argument("--cpu-sample", type=int, default=8192, help="tokens of the workload timed through the fp64 oracle (0: skip)")
@@ -64,6 +135,9 @@ def main() -> int:
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         return 2
+
+    if args.workload == "merge":
+        return bench_merge(args)
 
     import numpy as np
     import torch

@@ -60,7 +60,7 @@ Layout make_layout(const spes_moe_shape* s) {
   L.pub.yp = take(R * d * es);
   L.pub.dlogits = take(T * M * 4);
   L.pub.dgate = take(T * k * 4);
-  L.max_col_tiles = cdiv((long)f, 64) > mfma_rowdot_parts((int)f) ? cdiv((long)f, 64) : mfma_rowdot_parts((int)f);
+  L.max_col_tiles = cdiv((long)f, 64) + 1;   // covers both GEMM paths: f/64 (vector ALU) and 2*ceil(f/128) (matrix core)
   L.dgate_part = take((size_t)L.max_col_tiles * R * 4);
   L.da = take(R * f * es);
   L.db = take(R * f * es);
@@ -173,7 +173,7 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
                                  at<int>(ctx, L.row_token), at<float>(ctx, L.row_gate), simt_row_tile(),
                                  at<int>(ctx, L.tab_simt), mfma_row_tile(), at<int>(ctx, L.tab_mfma), L.max_tiles, s));
   prof_mark(0, "hist_scan_rank", s);
-  SPES_TRY(launch_permute(dt, x, at<int>(ctx, L.row_token), at<void>(ctx, L.pub.xp), R, d, s));
+  SPES_TRY(launch_permute(dt, x, at<int>(ctx, L.pub.inv), k, at<void>(ctx, L.pub.xp), T, d, s));
   prof_mark(0, "permute", s);
   // a = xp W_g^T, b = xp W_u^T, h = SiLU(a) * b
   {
@@ -367,6 +367,8 @@ SPES_API int spes_expert_warmup_merge(int32_t n_experts, int32_t dtype, int32_t 
     SPES_TRY(launch_warmup_mix(dtype, M, elems[m], top_K, alpha, src[m], dst[m], nbr, s));
   return SPES_OK;
 }
+
+SPES_API void spes_tune_tile(int32_t t) { mfma_set_tile(t); }
 
 SPES_API int spes_profile_enable(int32_t on) {
   if (on && !g_prof.created) {

@@ -32,6 +32,7 @@ struct GemmArgs {
   float* rowdot;          // kEpiDSwiglu: [gridDim.x, rowdot_stride] partial gate gradients
   long rowdot_stride;
   long b_ns, b_ks, b_gs;  // element strides of B along n, k, and per expert (kRaggedM)
+  int dbg;
   int npairs;             // kEpiStore/kEpiDSwiglu: (A,B) pairs accumulated into one result
   int Kdim;               // contraction length of each pair (kRaggedM) / total K (kGroupedK, uniform chunks)
   void* C[3];
@@ -53,7 +54,7 @@ struct GemmArgs {
   unsigned char group_expert[64];  // offset != nullptr: group g contracts rows [offset[e], offset[e+1]), e = group_expert[g]
 };
 
-__device__ __forceinline__ float sigmoidf_(float a) { return 1.0f / (1.0f + __expf(-a)); }
+__device__ __forceinline__ float sigmoidf_(float a) { return __builtin_amdgcn_rcpf(1.0f + __expf(-a)); }
 
 // launchers (storage type T of A/B/C unless stated); defined in gemm_simt.hip / gemm_mfma.hip
 int launch_gemm_simt(int dtype_a, int dtype_b, int mode, int epi, const GemmArgs& g, hipStream_t s);
@@ -61,6 +62,7 @@ int launch_gemm_mfma(int mode, int epi, bool a_kcontig, bool b_kcontig, const Ge
 int simt_row_tile();
 int simt_col_tile();
 int mfma_row_tile();
+void mfma_set_tile(int t);
 int mfma_rowdot_parts(int ndim);
 
 }  // namespace spes

@@ -1,15 +1,20 @@
 // Grouped bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate).
 //
-// Block tile 256 x 256 x 64, four wavefronts in a 2 x 2 arrangement, each owning a
-// 128 x 128 sub-tile as 4 x 4 MFMA tiles (256 accumulator registers per lane).
-// Operand tiles are staged global -> registers -> LDS with two LDS stages (128 KB),
-// so the loads of the next K-tile are in flight while the current one is multiplied.
-// Both operands live in LDS as [row][k] with a row pitch of 144 bytes (128 of data, 16
-// of padding): fragment reads (16 rows x one 16-byte chunk) and the transposed staging
-// writes (rows 8 apart) then spread over all 64 banks.
+// A 256-thread block (four wavefronts, 2 x 2) computes a BM x BN output tile, each
+// wavefront a (BM/2) x (BN/2) sub-tile as TM x TN MFMA tiles of 32 x 32 held in AGPRs.
+// Operand tiles are staged global -> registers -> LDS with two LDS stages:
+//   * the global loads of K-tile t+2 are issued right after the registers of tile t+1
+//     were written to LDS, so they have a whole iteration to land;
+//   * MFMA fragments are double-buffered in registers: the reads of k-step s+1 are
+//     issued before the MFMAs of k-step s, and the first fragments of the next K-tile
+//     are read (after the block barrier) under the last MFMAs of the current one.
+// Both operands live in LDS as [row][k] with a row pitch of BK*2+16 bytes, which
+// spreads the fragment reads (16 rows x one 16-byte chunk) over all banks.
 // An operand whose contraction index is the slow memory axis (the weights in the
 // input-gradient GEMMs, both operands of the weight-gradient GEMMs) is transposed in
 // registers (8x8 blocks, v_perm) on its way into LDS.
+// Loads are unconditional: rows and k beyond the operand are clamped to valid
+// addresses, the k tail is zeroed by select, surplus rows are never stored.
 //
 // The MFMA operands are swapped (weights tile as the "A" input) so that each lane ends
 // up holding runs of four consecutive output columns of one row: epilogues then work
@@ -26,97 +31,54 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int kChunks = BK / 8;                 // 16-byte chunks of data per LDS row
-constexpr int kPitch = kChunks + 1;             // row pitch in 16-byte units
-constexpr int kTileVec = BM * kPitch;           // uint4 per operand tile
 constexpr int kXcds = 8;
 
-__device__ __forceinline__ int lds_idx(int row, int chunk) { return row * kPitch + chunk; }
-
-// ---- staging of one operand tile --------------------------------------------------
-// K-contiguous operand: thread t owns chunk (t & 7) of rows (t >> 3) + 32 i, i = 0..7.
-struct RowOffs {
-  long o[8];   // element offset of the row start; < 0: row outside the operand (reads as zero)
+template <int BM_, int BN_, int BK_, int MINB_>
+struct Cfg {
+  static constexpr int BM = BM_, BN = BN_, BK = BK_, MINB = MINB_;
+  static constexpr int TM = BM / 64, TN = BN / 64;          // MFMA tiles per wavefront along m, n
+  static constexpr int KSTEPS = BK / 16;
+  static constexpr int CH = BK / 8;                         // 16-byte chunks of data per LDS row
+  static constexpr int PITCH = CH + 1;                      // row pitch in 16-byte units
+  static constexpr int RP = 256 / CH;                       // rows staged per pass (K-contiguous operand)
+  static constexpr int NA = BM / RP, NB = BN / RP;          // staging registers (uint4) per thread, K-contiguous
+  static constexpr int A_VEC = BM * PITCH, B_VEC = BN * PITCH;
+  static constexpr int STAGE_VEC = A_VEC + B_VEC;
+  // K-strided staging: 8x8 blocks, (rows/8)*CH of them per tile, spread over the 256 threads
+  static constexpr int ABLK = BM / 8 * CH, BBLK = BN / 8 * CH;
+  static constexpr int NAB = ABLK >= 256 ? ABLK / 256 : 1, NBB = BBLK >= 256 ? BBLK / 256 : 1;
+  static constexpr int RA = NA > 8 * NAB ? NA : 8 * NAB;    // staging register counts covering both kinds
+  static constexpr int RB = NB > 8 * NBB ? NB : 8 * NBB;
 };
 
-__device__ __forceinline__ void load_kcontig(const bf16_t* base, const RowOffs& ro, long k0, long k_end, uint4 (&r)[8]) {
-  const long k = k0 + (threadIdx.x & 7) * 8;
-  const bool kin = k < k_end;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    r[i] = make_uint4(0, 0, 0, 0);
-    if (kin && ro.o[i] >= 0) r[i] = *reinterpret_cast<const uint4*>(base + ro.o[i] + k);
-  }
-}
-
-// fused SwiGLU: rows i with ((i >> 1) & 1) set come from the second matrix (see the row map in the kernel)
-__device__ __forceinline__ void load_kcontig2(const bf16_t* base0, const bf16_t* base1, const RowOffs& ro, long k0, long k_end,
-                                              uint4 (&r)[8]) {
-  const long k = k0 + (threadIdx.x & 7) * 8;
-  const bool kin = k < k_end;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    r[i] = make_uint4(0, 0, 0, 0);
-    if (kin && ro.o[i] >= 0) r[i] = *reinterpret_cast<const uint4*>((((i >> 1) & 1) ? base1 : base0) + ro.o[i] + k);
-  }
-}
-
-__device__ __forceinline__ void store_kcontig(uint4* tile, const uint4 (&r)[8]) {
-  const int c = threadIdx.x & 7, r0 = threadIdx.x >> 3;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) tile[lds_idx(r0 + 32 * i, c)] = r[i];
-}
-
-// K-strided operand (element (row, k) at base + k*kstride + row): thread t owns the 8 x 8 block of
-// k-block (t & 7) and row-block (t >> 3): eight 16-byte loads along the rows, one per k.
-__device__ __forceinline__ void load_kstrided(const bf16_t* base, long kstride, const int* krows, long k0, long k_end, long row0,
-                                              long row_end, uint4 (&r)[8]) {
-  const long k = k0 + (threadIdx.x & 7) * 8;
-  const long row = row0 + (threadIdx.x >> 3) * 8;
-  const bool rin = row < row_end;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    r[j] = make_uint4(0, 0, 0, 0);
-    if (rin && k + j < k_end) {
-      const long kr = krows ? (long)krows[k + j] : k + j;
-      r[j] = *reinterpret_cast<const uint4*>(base + kr * kstride + row);
-    }
-  }
-}
-
-// in[j] holds rows n0..n0+7 at k_j; out row i gets k_0..k_7 of row n0+i
-__device__ __forceinline__ void store_kstrided(uint4* tile, const uint4 (&in)[8]) {
-  const int kb = threadIdx.x & 7, nb = threadIdx.x >> 3;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    uint32_t w[4];
-#pragma unroll
-    for (int m = 0; m < 4; ++m) {
-      // (k=2m, k=2m+1) of row i: low or high half of word i/2 of in[2m], in[2m+1]
-      const uint32_t lo_src = (i >> 1) == 0 ? in[2 * m].x : (i >> 1) == 1 ? in[2 * m].y : (i >> 1) == 2 ? in[2 * m].z : in[2 * m].w;
-      const uint32_t hi_src =
-          (i >> 1) == 0 ? in[2 * m + 1].x : (i >> 1) == 1 ? in[2 * m + 1].y : (i >> 1) == 2 ? in[2 * m + 1].z : in[2 * m + 1].w;
-      w[m] = (i & 1) ? __builtin_amdgcn_perm(hi_src, lo_src, 0x07060302u)    // high halves
-                     : __builtin_amdgcn_perm(hi_src, lo_src, 0x05040100u);   // low halves
-    }
-    tile[lds_idx(nb * 8 + i, kb)] = make_uint4(w[0], w[1], w[2], w[3]);
-  }
-}
-
-__device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ uint4 zero4() { return make_uint4(0, 0, 0, 0); }
+__device__ __forceinline__ uint4 sel4(bool keep, const uint4& v) { return keep ? v : zero4(); }
 __device__ __forceinline__ uint32_t pack2(float a, float b) { return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16); }
 
-// -----------------------------------------------------------------------------------
-template <int MODE, int EPI, bool A_KC, bool B_KC>
-__global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const GemmArgs g) {
-  __shared__ uint4 smem[2 * 2 * kTileVec];   // [stage][A|B][256 rows x 9 chunks] = 144 KB
+// out row i of an 8x8 block gets k_0..k_7 of row i; in[j] holds rows 0..7 at k_j
+__device__ __forceinline__ uint4 transpose_row(const uint4* in, int i) {
+  uint32_t w[4];
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    const uint32_t lo = (i >> 1) == 0 ? in[2 * m].x : (i >> 1) == 1 ? in[2 * m].y : (i >> 1) == 2 ? in[2 * m].z : in[2 * m].w;
+    const uint32_t hi =
+        (i >> 1) == 0 ? in[2 * m + 1].x : (i >> 1) == 1 ? in[2 * m + 1].y : (i >> 1) == 2 ? in[2 * m + 1].z : in[2 * m + 1].w;
+    w[m] = (i & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+  }
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+template <int MODE, int EPI, bool A_KC, bool B_KC, typename C>
+__global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs g) {
+  constexpr int BM = C::BM, BN = C::BN, BK = C::BK, TM = C::TM, TN = C::TN, CH = C::CH, RP = C::RP;
+  __shared__ uint4 smem[2 * C::STAGE_VEC];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, lhalf = lane >> 5;
   const int wm = wave >> 1, wn = wave & 1;
+  constexpr int BNO = (EPI == kEpiSwiglu) ? BN / 2 : BN;   // output columns per tile
 
   // ---- which tile ----
-  const int gx = (EPI == kEpiSwiglu) ? cdiv(g.Ndim, BN / 2) : cdiv(g.Ndim, BN);
+  const int gx = cdiv(g.Ndim, BNO);
   long total;
   if (MODE == kRaggedM) total = (long)(*g.n_tiles) * gx; else total = (long)g.n_groups * cdiv(g.Mdim, BM) * gx;
   const long per_xcd = (total + kXcds - 1) / kXcds;
@@ -146,37 +108,44 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const GemmArgs g) {
     }
     c_group = (long)grp * g.c_gs;
   }
-  // first output column of this tile; with the fused SwiGLU the 256 tile columns are 128 gate + 128 up columns
-  const long n0 = (EPI == kEpiSwiglu) ? (long)nt * (BN / 2) : (long)nt * BN;
+  const long n0 = (long)nt * BNO;
 
-  // ---- per-thread row offsets of K-contiguous operands (fixed over the K loop) ----
-  RowOffs arow, brow;
+  // ---- K-contiguous operands: source row of each staged tile row (clamped into the operand) ----
+  long arow[A_KC ? C::NA : 1];
+  long brow[B_KC ? C::NB : 1];
+  bool bsecond[B_KC ? C::NB : 1];   // fused SwiGLU: the row comes from the second matrix
+  if (A_KC) {
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    arow.o[i] = -1;
-    brow.o[i] = -1;
-    if (A_KC) {
-      const long m = m0 + (tid >> 3) + 32 * i;
-      if (m < m_end) arow.o[i] = ((MODE == kRaggedM && g.a_rows) ? (long)g.a_rows[m] : m) * g.a_ms;
+    for (int i = 0; i < C::NA; ++i) {
+      long m = m0 + tid / CH + RP * i;
+      m = m < m_end ? m : m_end - 1;
+      arow[i] = ((MODE == kRaggedM && g.a_rows) ? (long)g.a_rows[m] : m) * g.a_ms;
     }
-    if (B_KC) {
-      const int nl = (tid >> 3) + 32 * i;
+  }
+  if (B_KC) {
+#pragma unroll
+    for (int i = 0; i < C::NB; ++i) {
+      const int nl = tid / CH + RP * i;
+      long col;
+      bsecond[i] = false;
       if (EPI == kEpiSwiglu) {
-        // tile row nl: wave column nl/128, then 64 gate columns followed by the matching 64 up columns
-        // (rows with bit 6 of nl set, i.e. (i >> 1) & 1, read the up projection)
-        const long fcol = n0 + (nl >> 7) * 64 + (nl & 63);
-        if (fcol < g.Ndim) brow.o[i] = b_group + fcol * g.b_ns;
-      } else if (n0 + nl < g.Ndim) {
-        brow.o[i] = b_group + (n0 + nl) * g.b_ns;
+        // tile row nl -> wave column, then (BN/4) gate columns followed by the matching (BN/4) up columns
+        constexpr int W = BN / 2, H = BN / 4;
+        col = n0 + (nl / W) * H + (nl % H);
+        bsecond[i] = ((nl % W) / H) != 0;
+      } else {
+        col = n0 + nl;
       }
+      col = col < g.Ndim ? col : g.Ndim - 1;
+      brow[i] = b_group + col * g.b_ns;
     }
   }
 
-  f32x16 acc[4][4];   // [n sub-tile][m sub-tile]
+  f32x16 acc[TN][TM];
 #pragma unroll
-  for (int j = 0; j < 4; ++j)
+  for (int j = 0; j < TN; ++j)
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
 
@@ -185,68 +154,173 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const GemmArgs g) {
   const int nk = (int)((klen + BK - 1) / BK);
   const int nsteps = nk * npass;
 
-  uint4 ra[8], rb[8];
-  auto fetch = [&](int step) {
+  uint4 ra[C::RA], rb[C::RB];
+  unsigned a_keep = 0, b_keep = 0;   // which staged k (bit j; K-contiguous: all or none) lie inside the contraction range
+
+  // global -> registers for K-tile `step`
+  auto gload = [&](int step) {
     const int pass = step / nk;
     const long k0 = k_begin + (long)(step - pass * nk) * BK;
     if (A_KC) {
-      load_kcontig(reinterpret_cast<const bf16_t*>(g.A[pass]), arow, k0, k_end, ra);
+      const bf16_t* base = reinterpret_cast<const bf16_t*>(g.A[pass]);
+      const long k = k0 + (tid % CH) * 8;
+      const bool kin = k < k_end;
+      const long kc = kin ? k : k_begin;
+#pragma unroll
+      for (int i = 0; i < C::NA; ++i) ra[i] = *reinterpret_cast<const uint4*>(base + arow[i] + kc);
+      a_keep = kin ? 0xffu : 0u;
     } else {
-      load_kstrided(reinterpret_cast<const bf16_t*>(g.A[pass]), g.a_ks, g.a_rows, k0, k_end, m0, m_end, ra);
+      const bf16_t* base = reinterpret_cast<const bf16_t*>(g.A[pass]);
+#pragma unroll
+      for (int q = 0; q < C::NAB; ++q) {
+        const int blk = tid + 256 * q;
+        if (C::ABLK >= 256 || blk < C::ABLK) {
+          const long k = k0 + (blk % CH) * 8;
+          long row = m0 + (blk / CH) * 8;
+          row = row < m_end ? row : m0;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const long kj = k + j < k_end ? k + j : k_end - 1;
+            const long kr = g.a_rows ? (long)g.a_rows[kj] : kj;
+            ra[q * 8 + j] = *reinterpret_cast<const uint4*>(base + kr * g.a_ks + row);
+          }
+          const long left = k_end - k;
+          a_keep = left >= 8 ? 0xffu : left <= 0 ? 0u : ((1u << left) - 1u);   // same k for every q: ABLK >= 256 only if CH | 256
+        }
+      }
     }
     if (B_KC) {
-      if (EPI == kEpiSwiglu)
-        load_kcontig2(reinterpret_cast<const bf16_t*>(g.B[0]), reinterpret_cast<const bf16_t*>(g.B[1]), brow, k0, k_end, rb);
-      else
-        load_kcontig(reinterpret_cast<const bf16_t*>(g.B[pass]), brow, k0, k_end, rb);
+      const bf16_t* base0 = reinterpret_cast<const bf16_t*>(g.B[(EPI == kEpiSwiglu) ? 0 : pass]);
+      const bf16_t* base1 = reinterpret_cast<const bf16_t*>(g.B[1]);
+      const long k = k0 + (tid % CH) * 8;
+      const bool kin = k < k_end;
+      const long kc = kin ? k : k_begin;
+#pragma unroll
+      for (int i = 0; i < C::NB; ++i) {
+        const bf16_t* base = (EPI == kEpiSwiglu && bsecond[i]) ? base1 : base0;
+        rb[i] = *reinterpret_cast<const uint4*>(base + brow[i] + kc);
+      }
+      b_keep = kin ? 0xffu : 0u;
     } else {
-      load_kstrided(reinterpret_cast<const bf16_t*>(g.B[pass]) + b_group, g.b_ks, nullptr, k0, k_end, n0, g.Ndim, rb);
+      const bf16_t* base = reinterpret_cast<const bf16_t*>(g.B[pass]) + b_group;
+#pragma unroll
+      for (int q = 0; q < C::NBB; ++q) {
+        const int blk = tid + 256 * q;
+        if (C::BBLK >= 256 || blk < C::BBLK) {
+          const long k = k0 + (blk % CH) * 8;
+          long row = n0 + (blk / CH) * 8;
+          row = row < g.Ndim ? row : n0;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const long kj = k + j < k_end ? k + j : k_end - 1;
+            rb[q * 8 + j] = *reinterpret_cast<const uint4*>(base + kj * g.b_ks + row);
+          }
+          const long left = k_end - k;
+          b_keep = left >= 8 ? 0xffu : left <= 0 ? 0u : ((1u << left) - 1u);
+        }
+      }
     }
   };
+
+  // registers -> LDS stage
   auto stash = [&](int stage) {
-    uint4* ta = smem + stage * 2 * kTileVec;
-    uint4* tb = ta + kTileVec;
-    if (A_KC) store_kcontig(ta, ra); else store_kstrided(ta, ra);
-    if (B_KC) store_kcontig(tb, rb); else store_kstrided(tb, rb);
+    uint4* ta = smem + stage * C::STAGE_VEC;
+    uint4* tb = ta + C::A_VEC;
+    if (A_KC) {
+#pragma unroll
+      for (int i = 0; i < C::NA; ++i) ta[(tid / CH + RP * i) * C::PITCH + tid % CH] = sel4(a_keep != 0, ra[i]);
+    } else {
+#pragma unroll
+      for (int q = 0; q < C::NAB; ++q) {
+        const int blk = tid + 256 * q;
+        if (C::ABLK >= 256 || blk < C::ABLK) {
+          if (a_keep != 0xffu) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) ra[q * 8 + j] = sel4((a_keep >> j) & 1u, ra[q * 8 + j]);
+          }
+#pragma unroll
+          for (int i = 0; i < 8; ++i) ta[((blk / CH) * 8 + i) * C::PITCH + blk % CH] = transpose_row(&ra[q * 8], i);
+        }
+      }
+    }
+    if (B_KC) {
+#pragma unroll
+      for (int i = 0; i < C::NB; ++i) tb[(tid / CH + RP * i) * C::PITCH + tid % CH] = sel4(b_keep != 0, rb[i]);
+    } else {
+#pragma unroll
+      for (int q = 0; q < C::NBB; ++q) {
+        const int blk = tid + 256 * q;
+        if (C::BBLK >= 256 || blk < C::BBLK) {
+          if (b_keep != 0xffu) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) rb[q * 8 + j] = sel4((b_keep >> j) & 1u, rb[q * 8 + j]);
+          }
+#pragma unroll
+          for (int i = 0; i < 8; ++i) tb[((blk / CH) * 8 + i) * C::PITCH + blk % CH] = transpose_row(&rb[q * 8], i);
+        }
+      }
+    }
+  };
+
+  bf16x8 fa[2][TM], fb[2][TN];
+  auto read_frags = [&](int stage, int ks, int set) {
+    const uint4* ta = smem + stage * C::STAGE_VEC;
+    const uint4* tb = ta + C::A_VEC;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+      fa[set][i] = __builtin_bit_cast(bf16x8, ta[(wm * (BM / 2) + i * 32 + l32) * C::PITCH + ks * 2 + lhalf]);
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+      fb[set][j] = __builtin_bit_cast(bf16x8, tb[(wn * (BN / 2) + j * 32 + l32) * C::PITCH + ks * 2 + lhalf]);
+  };
+  auto mfmas = [&](int set) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int i = 0; i < TM; ++i) acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[j][i], 0, 0, 0);
   };
 
   if (nsteps > 0) {
-    fetch(0);
+    gload(0);
     stash(0);
-  }
-  __syncthreads();
-  for (int step = 0; step < nsteps; ++step) {
-    const int cur = step & 1;
-    if (step + 1 < nsteps) fetch(step + 1);
-    const uint4* ta = smem + cur * 2 * kTileVec;
-    const uint4* tb = ta + kTileVec;
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 af[4], bfr[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) af[i] = __builtin_bit_cast(bf16x8, ta[lds_idx(wm * 128 + i * 32 + l32, ks * 2 + lhalf)]);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) bfr[j] = __builtin_bit_cast(bf16x8, tb[lds_idx(wn * 128 + j * 32 + l32, ks * 2 + lhalf)]);
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[j][i], 0, 0, 0);
-    }
-    if (step + 1 < nsteps) stash(cur ^ 1);
+    if (nsteps > 1) gload(1);
     __syncthreads();
+    read_frags(0, 0, 0);
+    constexpr int WRITE_KS = C::KSTEPS >= 4 ? 1 : 0;
+    for (int t = 0; t < nsteps; ++t) {
+      const int cur = t & 1;
+#pragma unroll
+      for (int ks = 0; ks < C::KSTEPS; ++ks) {
+        const int set = ks & 1;
+        if (ks + 1 < C::KSTEPS) {
+          read_frags(cur, ks + 1, set ^ 1);
+        } else if (t + 1 < nsteps) {
+          read_frags(cur ^ 1, 0, set ^ 1);     // next K-tile, published by the barrier below
+        }
+        if (ks == WRITE_KS) {
+          if (t + 1 < nsteps && !(g.dbg & 2)) stash(cur ^ 1);
+          if (t + 2 < nsteps && !(g.dbg & 1)) gload(t + 2);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (!(g.dbg & 4)) mfmas(set);
+        __builtin_amdgcn_sched_barrier(0);
+        if (ks == C::KSTEPS - 2) __syncthreads();
+      }
+    }
   }
 
   // ---- epilogue: lane holds row m = .. + l32 and, per register group gq, columns gq*8 + lhalf*4 + 0..3 ----
+  if (g.dbg & 8) return;
   if (EPI == kEpiStore) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const long m = m0 + wm * 128 + i * 32 + l32;
+    for (int i = 0; i < TM; ++i) {
+      const long m = m0 + wm * (BM / 2) + i * 32 + l32;
       if (m >= m_end) continue;
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
-          const long n = n0 + wn * 128 + j * 32 + gq * 8 + lhalf * 4;
+          const long n = n0 + wn * (BN / 2) + j * 32 + gq * 8 + lhalf * 4;
           if (n >= g.Ndim) continue;
           const long ci = c_group + m * g.c_ms + n;
           const float v0 = acc[j][i][gq * 4], v1 = acc[j][i][gq * 4 + 1], v2 = acc[j][i][gq * 4 + 2], v3 = acc[j][i][gq * 4 + 3];
@@ -262,21 +336,21 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const GemmArgs g) {
     }
   } else if (EPI == kEpiSwiglu) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const long m = m0 + wm * 128 + i * 32 + l32;
+    for (int i = 0; i < TM; ++i) {
+      const long m = m0 + wm * (BM / 2) + i * 32 + l32;
       if (m >= m_end) continue;
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < TN / 2; ++j)
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
-          const long n = n0 + wn * 64 + j * 32 + gq * 8 + lhalf * 4;
+          const long n = n0 + wn * (BN / 4) + j * 32 + gq * 8 + lhalf * 4;
           if (n >= g.Ndim) continue;
           const long ci = m * g.c_ms + n;
           float a[4], b[4], h[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             a[e] = acc[j][i][gq * 4 + e];
-            b[e] = acc[j + 2][i][gq * 4 + e];
+            b[e] = acc[j + TN / 2][i][gq * 4 + e];
             h[e] = a[e] * sigmoidf_(a[e]) * b[e];
           }
           *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.C[0]) + ci) = make_float4(a[0], a[1], a[2], a[3]);
@@ -286,17 +360,17 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const GemmArgs g) {
     }
   } else {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const long m = m0 + wm * 128 + i * 32 + l32;
+    for (int i = 0; i < TM; ++i) {
+      const long m = m0 + wm * (BM / 2) + i * 32 + l32;
       const bool min_ = m < m_end;
       const float rs = min_ ? g.row_scale[m] : 0.f;
       float dot = 0.f;
       if (min_) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
           for (int gq = 0; gq < 4; ++gq) {
-            const long n = n0 + wn * 128 + j * 32 + gq * 8 + lhalf * 4;
+            const long n = n0 + wn * (BN / 2) + j * 32 + gq * 8 + lhalf * 4;
             if (n >= g.Ndim) continue;
             const long ci = m * g.c_ms + n;
             const float4 av = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(g.E[0]) + ci);
@@ -307,11 +381,12 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const GemmArgs g) {
             for (int e = 0; e < 4; ++e) {
               const float u = acc[j][i][gq * 4 + e];
               const float sg = sigmoidf_(a[e]);
-              const float h = a[e] * sg * b[e];
+              const float as = a[e] * sg;          // SiLU(a)
+              const float h = as * b[e];
               dot = fmaf(u, h, dot);
               const float dh = rs * u;
-              da[e] = dh * b[e] * sg * (1.f + a[e] * (1.f - sg));
-              db[e] = dh * a[e] * sg;
+              da[e] = dh * b[e] * (sg + as * (1.f - sg));
+              db[e] = dh * as;
               hg[e] = rs * h;
             }
             *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.C[0]) + ci) = make_uint2(pack2(da[0], da[1]), pack2(da[2], da[3]));
@@ -326,22 +401,38 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const GemmArgs g) {
   }
 }
 
-template <int MODE, int EPI, bool A_KC, bool B_KC>
-int launch(const GemmArgs& g, hipStream_t s) {
-  const int gx = (EPI == kEpiSwiglu) ? cdiv(g.Ndim, BN / 2) : cdiv(g.Ndim, BN);
-  long total = (MODE == kRaggedM) ? (long)g.max_tiles * gx : (long)g.n_groups * cdiv(g.Mdim, BM) * gx;
+// tile configurations: 256 x 128 x 32 with two blocks per CU (2 x 60 KB of LDS, 128 accumulators per lane),
+// or 256 x 256 x 64 with one block per CU (144 KB of LDS, 256 accumulators per lane)
+typedef Cfg<256, 128, 32, 2> Small;
+typedef Cfg<256, 256, 64, 1> Large;
+int g_tile = 0;   // 0: Small, 1: Large
+int g_dbg = 0;
+
+template <int MODE, int EPI, bool A_KC, bool B_KC, typename C>
+int launch_cfg(const GemmArgs& g, hipStream_t s) {
+  const int bno = (EPI == kEpiSwiglu) ? C::BN / 2 : C::BN;
+  const int gx = cdiv(g.Ndim, bno);
+  long total = (MODE == kRaggedM) ? (long)g.max_tiles * gx : (long)g.n_groups * cdiv(g.Mdim, C::BM) * gx;
   if (total <= 0) return SPES_OK;
   total = (total + kXcds - 1) / kXcds * kXcds;
-  hipLaunchKernelGGL((gemm_mfma_kernel<MODE, EPI, A_KC, B_KC>), dim3((unsigned)total), dim3(256), 0, s, g);
+  GemmArgs gg = g;
+  gg.dbg = g_dbg;
+  hipLaunchKernelGGL((gemm_mfma_kernel<MODE, EPI, A_KC, B_KC, C>), dim3((unsigned)total), dim3(256), 0, s, gg);
   return hipGetLastError() == hipSuccess ? SPES_OK : SPES_EHIP;
+}
+
+template <int MODE, int EPI, bool A_KC, bool B_KC>
+int launch(const GemmArgs& g, hipStream_t s) {
+  if (g_tile == 1) return launch_cfg<MODE, EPI, A_KC, B_KC, Large>(g, s);
+  return launch_cfg<MODE, EPI, A_KC, B_KC, Small>(g, s);
 }
 
 }  // namespace
 
-int mfma_row_tile() { return BM; }
-// number of gate-gradient partials per row that the kEpiDSwiglu epilogue writes for Ndim columns
-int mfma_rowdot_parts(int ndim) { return 2 * cdiv(ndim, BN); }
-
+void mfma_set_tile(int t) { g_tile = t & 0xff; g_dbg = t >> 8; }
+int mfma_row_tile() { return 256; }
+// number of gate-gradient partials per row that the kEpiDSwiglu epilogue writes for ndim columns
+int mfma_rowdot_parts(int ndim) { return 2 * cdiv(ndim, g_tile == 1 ? Large::BN : Small::BN); }
 // bf16 operands only.  a_kcontig / b_kcontig: the contraction index is the fast memory axis of that operand.
 int launch_gemm_mfma(int mode, int epi, bool a_kcontig, bool b_kcontig, const GemmArgs& g, hipStream_t s) {
   if (mode == kRaggedM) {

@@ -17,7 +17,7 @@ int launch_gating_bwd(const float* logits, const float* lse, const int* idx, con
                       hipStream_t s);
 
 // movement.hip (dtype = spes_dtype of the storage type)
-int launch_permute(int dtype, const void* x, const int* row_token, void* xp, long R, int d, hipStream_t s);
+int launch_permute(int dtype, const void* x, const int* inv, int k, void* xp, int T, int d, hipStream_t s);
 int launch_combine(int dtype, const void* yp, const int* inv, const float* gate, void* y, int T, int d, int k, hipStream_t s);
 int launch_dx_gather(int dtype, const void* dxp, const int* inv, const float* dlogits, const void* w_router, void* dx, int T,
                      int d, int k, int M, hipStream_t s);

@@ -7,24 +7,26 @@
 namespace spes {
 namespace {
 
-// xp[r,:] = x[row_token[r], :]
+// xp[inv[t*k+j], :] = x[t, :] for j < k: every input row is read once and written to its k places
 template <typename T>
-__global__ __launch_bounds__(256) void permute_kernel(const T* __restrict__ x, const int* __restrict__ row_token,
+__global__ __launch_bounds__(256) void permute_kernel(const T* __restrict__ x, const int* __restrict__ inv, int k,
                                                       T* __restrict__ xp, long total_vec, int nvec, int d) {
   constexpr int N = Vec16<T>::N;
   const long stride = (long)gridDim.x * 256;
   for (long v = (long)blockIdx.x * 256 + threadIdx.x; v < total_vec; v += stride) {
-    const long r = v / nvec;
-    const int c = (int)(v - r * nvec);
-    const int t = row_token[r];
+    const long t = v / nvec;
+    const int c = (int)(v - t * nvec);
     Vec16<T> q;
-    q.load(x + (long)t * d + c * N);
-    q.store(xp + r * d + c * N);
+    q.load(x + t * d + c * N);
+    for (int j = 0; j < k; ++j) {
+      const long r = inv[t * k + j];
+      q.store(xp + r * d + c * N);
+    }
   }
 }
 
-// y[t,:] = sum_j gate[t,j] * yp[inv[t*k+j], :]
-template <typename T>
+// y[t,:] = sum_j gate[t,j] * yp[inv[t*k+j], :]; KU > 0: k == KU, all k rows are requested before the first is used
+template <typename T, int KU>
 __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ yp, const int* __restrict__ inv,
                                                       const float* __restrict__ gate, T* __restrict__ y, long total_vec,
                                                       int nvec, int d, int k) {
@@ -36,15 +38,33 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ yp, 
     float acc[N];
 #pragma unroll
     for (int i = 0; i < N; ++i) acc[i] = 0.f;
-    for (int j = 0; j < k; ++j) {
-      const long r = inv[t * k + j];
-      const float g = gate[t * k + j];
-      Vec16<T> q;
-      q.load(yp + r * d + c * N);
-      float f[N];
-      q.unpack(f);
+    if (KU > 0) {
+      Vec16<T> q[KU > 0 ? KU : 1];
+      float g[KU > 0 ? KU : 1];
 #pragma unroll
-      for (int i = 0; i < N; ++i) acc[i] = fmaf(g, f[i], acc[i]);
+      for (int j = 0; j < KU; ++j) {
+        const long r = inv[t * KU + j];
+        g[j] = gate[t * KU + j];
+        q[j].load(yp + r * d + c * N);
+      }
+#pragma unroll
+      for (int j = 0; j < KU; ++j) {
+        float f[N];
+        q[j].unpack(f);
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] = fmaf(g[j], f[i], acc[i]);
+      }
+    } else {
+      for (int j = 0; j < k; ++j) {
+        const long r = inv[t * k + j];
+        const float g = gate[t * k + j];
+        Vec16<T> q;
+        q.load(yp + r * d + c * N);
+        float f[N];
+        q.unpack(f);
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] = fmaf(g, f[i], acc[i]);
+      }
     }
     Vec16<T> o;
     o.pack(acc);
@@ -117,30 +137,37 @@ inline int ok() { return hipGetLastError() == hipSuccess ? SPES_OK : SPES_EHIP; 
 
 }  // namespace
 
-int launch_permute(int dtype, const void* x, const int* row_token, void* xp, long R, int d, hipStream_t s) {
-  if (R == 0) return SPES_OK;
+int launch_permute(int dtype, const void* x, const int* inv, int k, void* xp, int T, int d, hipStream_t s) {
   if (dtype == SPES_F32) {
     const int nvec = d / 4;
-    hipLaunchKernelGGL(permute_kernel<float>, dim3(flat_grid(R * nvec)), dim3(256), 0, s, (const float*)x, row_token, (float*)xp,
-                       R * nvec, nvec, d);
+    hipLaunchKernelGGL(permute_kernel<float>, dim3(flat_grid((long)T * nvec)), dim3(256), 0, s, (const float*)x, inv, k, (float*)xp,
+                       (long)T * nvec, nvec, d);
   } else {
     const int nvec = d / 8;
-    hipLaunchKernelGGL(permute_kernel<bf16_t>, dim3(flat_grid(R * nvec)), dim3(256), 0, s, (const bf16_t*)x, row_token,
-                       (bf16_t*)xp, R * nvec, nvec, d);
+    hipLaunchKernelGGL(permute_kernel<bf16_t>, dim3(flat_grid((long)T * nvec)), dim3(256), 0, s, (const bf16_t*)x, inv, k,
+                       (bf16_t*)xp, (long)T * nvec, nvec, d);
   }
   return ok();
 }
 
+template <typename T>
+void combine_dispatch(const void* yp, const int* inv, const float* gate, void* y, int Tn, int d, int k, hipStream_t s) {
+  const int nvec = d / Vec16<T>::N;
+  const long total = (long)Tn * nvec;
+  const dim3 grid(flat_grid(total));
+#define SPES_COMBINE(KU) \
+  hipLaunchKernelGGL((combine_kernel<T, KU>), grid, dim3(256), 0, s, (const T*)yp, inv, gate, (T*)y, total, nvec, d, k)
+  if (k == 8) SPES_COMBINE(8);
+  else if (k == 4) SPES_COMBINE(4);
+  else if (k == 2) SPES_COMBINE(2);
+  else if (k == 1) SPES_COMBINE(1);
+  else SPES_COMBINE(0);
+#undef SPES_COMBINE
+}
+
 int launch_combine(int dtype, const void* yp, const int* inv, const float* gate, void* y, int T, int d, int k, hipStream_t s) {
-  if (dtype == SPES_F32) {
-    const int nvec = d / 4;
-    hipLaunchKernelGGL(combine_kernel<float>, dim3(flat_grid((long)T * nvec)), dim3(256), 0, s, (const float*)yp, inv, gate,
-                       (float*)y, (long)T * nvec, nvec, d, k);
-  } else {
-    const int nvec = d / 8;
-    hipLaunchKernelGGL(combine_kernel<bf16_t>, dim3(flat_grid((long)T * nvec)), dim3(256), 0, s, (const bf16_t*)yp, inv, gate,
-                       (bf16_t*)y, (long)T * nvec, nvec, d, k);
-  }
+  if (dtype == SPES_F32) combine_dispatch<float>(yp, inv, gate, y, T, d, k, s);
+  else combine_dispatch<bf16_t>(yp, inv, gate, y, T, d, k, s);
   return ok();
 }
 
