@@ -323,7 +323,7 @@ SPES_API int spes_expert_merge(int32_t n_experts, int64_t elems, int32_t dtype, 
 }
 
 static int gram_groups(int64_t elems_in) {
-  long g = (elems_in + 4095) / 4096;
+  long g = (elems_in + 8191) / 8192;
   if (g > 1024) g = 1024;
   if (g < 1) g = 1;
   return (int)g;
@@ -351,7 +351,7 @@ SPES_API int spes_expert_warmup_merge(int32_t n_experts, int32_t dtype, int32_t 
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int M = n_experts;
   const int ng = gram_groups(elems_in);
-  const long kchunk = (elems_in + ng - 1) / ng;
+  const long kchunk = ((elems_in + ng - 1) / ng + 63) / 64 * 64;   // whole K-tiles per group
   {
     // Gram matrix of the flattened input projections, split along the long contraction
     GemmArgs g = blank();
@@ -360,15 +360,14 @@ SPES_API int spes_expert_warmup_merge(int32_t n_experts, int32_t dtype, int32_t 
     g.Kdim = (int)elems_in; g.kchunk = (int)kchunk; g.n_groups = ng;
     g.Mdim = M; g.Ndim = M;
     g.C[0] = scratch; g.c_ms = M; g.c_gs = (long)M * M; g.c_f32 = 1;
-    SPES_TRY(launch_gemm_simt(dtype, dtype, kGroupedK, kEpiStore, g, s));
+    if (dtype == SPES_BF16 && M % 4 == 0) SPES_TRY(launch_gemm_mfma(kGroupedK, kEpiStore, true, true, g, s));
+    else SPES_TRY(launch_gemm_simt(dtype, dtype, kGroupedK, kEpiStore, g, s));
   }
   SPES_TRY(launch_sim_topk(static_cast<const float*>(scratch), ng, M, top_K, sim, nbr, s));
   for (int m = 0; m < n_mats; ++m)
     SPES_TRY(launch_warmup_mix(dtype, M, elems[m], top_K, alpha, src[m], dst[m], nbr, s));
   return SPES_OK;
 }
-
-SPES_API void spes_tune_tile(int32_t t) { mfma_set_tile(t); }
 
 SPES_API int spes_profile_enable(int32_t on) {
   if (on && !g_prof.created) {

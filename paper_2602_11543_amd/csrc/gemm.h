@@ -32,7 +32,6 @@ struct GemmArgs {
   float* rowdot;          // kEpiDSwiglu: [gridDim.x, rowdot_stride] partial gate gradients
   long rowdot_stride;
   long b_ns, b_ks, b_gs;  // element strides of B along n, k, and per expert (kRaggedM)
-  int dbg;
   int npairs;             // kEpiStore/kEpiDSwiglu: (A,B) pairs accumulated into one result
   int Kdim;               // contraction length of each pair (kRaggedM) / total K (kGroupedK, uniform chunks)
   void* C[3];
@@ -62,7 +61,6 @@ int launch_gemm_mfma(int mode, int epi, bool a_kcontig, bool b_kcontig, const Ge
 int simt_row_tile();
 int simt_col_tile();
 int mfma_row_tile();
-void mfma_set_tile(int t);
 int mfma_rowdot_parts(int ndim);
 
 }  // namespace spes

@@ -3,8 +3,11 @@
 // A 256-thread block (four wavefronts, 2 x 2) computes a BM x BN output tile, each
 // wavefront a (BM/2) x (BN/2) sub-tile as TM x TN MFMA tiles of 32 x 32 held in AGPRs.
 // Operand tiles are staged global -> registers -> LDS with two LDS stages:
-//   * the global loads of K-tile t+2 are issued right after the registers of tile t+1
-//     were written to LDS, so they have a whole iteration to land;
+//   * a register is written to LDS (K-tile t+1) and at once reloaded from global
+//     memory (K-tile t+2), so every load has a whole iteration to land;
+//   * those writes and loads are issued one at a time between MFMAs, and the main
+//     loop is a single basic block, so the matrix pipe never waits behind a burst
+//     of memory instructions and the compiler's wait counts are exact;
 //   * MFMA fragments are double-buffered in registers: the reads of k-step s+1 are
 //     issued before the MFMAs of k-step s, and the first fragments of the next K-tile
 //     are read (after the block barrier) under the last MFMAs of the current one.
@@ -52,7 +55,11 @@ struct Cfg {
 };
 
 __device__ __forceinline__ uint4 zero4() { return make_uint4(0, 0, 0, 0); }
-__device__ __forceinline__ uint4 sel4(bool keep, const uint4& v) { return keep ? v : zero4(); }
+// branch-free: the main loop must stay one basic block so that the compiler counts outstanding loads exactly
+__device__ __forceinline__ uint4 sel4(bool keep, const uint4& v) {
+  const uint32_t m = keep ? 0xffffffffu : 0u;
+  return make_uint4(v.x & m, v.y & m, v.z & m, v.w & m);
+}
 __device__ __forceinline__ uint32_t pack2(float a, float b) { return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16); }
 
 // out row i of an 8x8 block gets k_0..k_7 of row i; in[j] holds rows 0..7 at k_j
@@ -154,110 +161,128 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   const int nk = (int)((klen + BK - 1) / BK);
   const int nsteps = nk * npass;
 
+  // ---- staging registers and the pieces of the global -> register -> LDS pipeline ----
+  // The loads and LDS writes of one K-tile are cut into pieces that the main loop issues one at a time between
+  // MFMAs: a wavefront that issues sixteen 1 KB loads (or writes) back to back sits behind the memory queues for
+  // well over a thousand cycles with its matrix pipe idle, while one piece every few MFMAs is absorbed for free.
+  //   K-contiguous operand: piece i = write register i to LDS (tile t+1), then reload it (tile t+2).
+  //   K-strided operand:    pieces 0..7 = transpose + write row i of the 8x8 block, pieces 8..15 = reload k-row j.
   uint4 ra[C::RA], rb[C::RB];
-  unsigned a_keep = 0, b_keep = 0;   // which staged k (bit j; K-contiguous: all or none) lie inside the contraction range
+  unsigned a_keep = 0, b_keep = 0;       // k inside the contraction range, for the tile held in ra / rb (bit j; K-contiguous: all/none)
+  unsigned a_keep_n = 0, b_keep_n = 0;   // the same for the tile being loaded
+  constexpr int NPA = A_KC ? C::NA : 16 * C::NAB;
+  constexpr int NPB = B_KC ? C::NB : 16 * C::NBB;
+  constexpr int NP = NPA + NPB;
 
-  // global -> registers for K-tile `step`
-  auto gload = [&](int step) {
+  // scalar coordinates of the K-tile being loaded
+  const bf16_t* la_base = nullptr;
+  const bf16_t* lb_base = nullptr;
+  long l_k0 = 0;
+  auto set_load_tile = [&](int step) {
     const int pass = step / nk;
-    const long k0 = k_begin + (long)(step - pass * nk) * BK;
+    l_k0 = k_begin + (long)(step - pass * nk) * BK;
+    la_base = reinterpret_cast<const bf16_t*>(g.A[pass]);
+    lb_base = reinterpret_cast<const bf16_t*>(g.B[(EPI == kEpiSwiglu) ? 0 : pass]) + (B_KC ? 0 : b_group);
     if (A_KC) {
-      const bf16_t* base = reinterpret_cast<const bf16_t*>(g.A[pass]);
-      const long k = k0 + (tid % CH) * 8;
-      const bool kin = k < k_end;
-      const long kc = kin ? k : k_begin;
-#pragma unroll
-      for (int i = 0; i < C::NA; ++i) ra[i] = *reinterpret_cast<const uint4*>(base + arow[i] + kc);
-      a_keep = kin ? 0xffu : 0u;
+      a_keep_n = (l_k0 + (tid % CH) * 8 < k_end) ? 0xffu : 0u;
     } else {
-      const bf16_t* base = reinterpret_cast<const bf16_t*>(g.A[pass]);
-#pragma unroll
-      for (int q = 0; q < C::NAB; ++q) {
-        const int blk = tid + 256 * q;
-        if (C::ABLK >= 256 || blk < C::ABLK) {
-          const long k = k0 + (blk % CH) * 8;
-          long row = m0 + (blk / CH) * 8;
-          row = row < m_end ? row : m0;
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const long kj = k + j < k_end ? k + j : k_end - 1;
-            const long kr = g.a_rows ? (long)g.a_rows[kj] : kj;
-            ra[q * 8 + j] = *reinterpret_cast<const uint4*>(base + kr * g.a_ks + row);
-          }
-          const long left = k_end - k;
-          a_keep = left >= 8 ? 0xffu : left <= 0 ? 0u : ((1u << left) - 1u);   // same k for every q: ABLK >= 256 only if CH | 256
-        }
-      }
+      const long left = k_end - (l_k0 + (tid % CH) * 8);
+      a_keep_n = left >= 8 ? 0xffu : left <= 0 ? 0u : ((1u << left) - 1u);
     }
     if (B_KC) {
-      const bf16_t* base0 = reinterpret_cast<const bf16_t*>(g.B[(EPI == kEpiSwiglu) ? 0 : pass]);
-      const bf16_t* base1 = reinterpret_cast<const bf16_t*>(g.B[1]);
-      const long k = k0 + (tid % CH) * 8;
-      const bool kin = k < k_end;
-      const long kc = kin ? k : k_begin;
-#pragma unroll
-      for (int i = 0; i < C::NB; ++i) {
-        const bf16_t* base = (EPI == kEpiSwiglu && bsecond[i]) ? base1 : base0;
-        rb[i] = *reinterpret_cast<const uint4*>(base + brow[i] + kc);
-      }
-      b_keep = kin ? 0xffu : 0u;
+      b_keep_n = (l_k0 + (tid % CH) * 8 < k_end) ? 0xffu : 0u;
     } else {
-      const bf16_t* base = reinterpret_cast<const bf16_t*>(g.B[pass]) + b_group;
-#pragma unroll
-      for (int q = 0; q < C::NBB; ++q) {
-        const int blk = tid + 256 * q;
-        if (C::BBLK >= 256 || blk < C::BBLK) {
-          const long k = k0 + (blk % CH) * 8;
-          long row = n0 + (blk / CH) * 8;
-          row = row < g.Ndim ? row : n0;
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const long kj = k + j < k_end ? k + j : k_end - 1;
-            rb[q * 8 + j] = *reinterpret_cast<const uint4*>(base + kj * g.b_ks + row);
-          }
-          const long left = k_end - k;
-          b_keep = left >= 8 ? 0xffu : left <= 0 ? 0u : ((1u << left) - 1u);
-        }
-      }
+      const long left = k_end - (l_k0 + (tid % CH) * 8);
+      b_keep_n = left >= 8 ? 0xffu : left <= 0 ? 0u : ((1u << left) - 1u);
     }
   };
 
-  // registers -> LDS stage
-  auto stash = [&](int stage) {
-    uint4* ta = smem + stage * C::STAGE_VEC;
-    uint4* tb = ta + C::A_VEC;
+  auto load_a = [&](int idx) {   // idx: register (K-contiguous) or q*8+j (K-strided)
     if (A_KC) {
-#pragma unroll
-      for (int i = 0; i < C::NA; ++i) ta[(tid / CH + RP * i) * C::PITCH + tid % CH] = sel4(a_keep != 0, ra[i]);
+      const long k = l_k0 + (tid % CH) * 8;
+      ra[idx] = *reinterpret_cast<const uint4*>(la_base + arow[idx] + (a_keep_n ? k : k_begin));
     } else {
-#pragma unroll
-      for (int q = 0; q < C::NAB; ++q) {
-        const int blk = tid + 256 * q;
-        if (C::ABLK >= 256 || blk < C::ABLK) {
-          if (a_keep != 0xffu) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) ra[q * 8 + j] = sel4((a_keep >> j) & 1u, ra[q * 8 + j]);
-          }
-#pragma unroll
-          for (int i = 0; i < 8; ++i) ta[((blk / CH) * 8 + i) * C::PITCH + blk % CH] = transpose_row(&ra[q * 8], i);
-        }
+      const int q = idx >> 3, j = idx & 7;
+      const int blk = tid + 256 * q;
+      if (C::ABLK >= 256 || blk < C::ABLK) {
+        const long k = l_k0 + (blk % CH) * 8 + j;
+        long row = m0 + (blk / CH) * 8;
+        row = row < m_end ? row : m0;
+        const long kj = k < k_end ? k : k_end - 1;
+        const long kr = g.a_rows ? (long)g.a_rows[kj] : kj;
+        ra[idx] = *reinterpret_cast<const uint4*>(la_base + kr * g.a_ks + row);
       }
     }
+  };
+  auto load_b = [&](int idx) {
     if (B_KC) {
-#pragma unroll
-      for (int i = 0; i < C::NB; ++i) tb[(tid / CH + RP * i) * C::PITCH + tid % CH] = sel4(b_keep != 0, rb[i]);
+      const long k = l_k0 + (tid % CH) * 8;
+      const bf16_t* base = (EPI == kEpiSwiglu && bsecond[idx]) ? reinterpret_cast<const bf16_t*>(g.B[1]) : lb_base;
+      rb[idx] = *reinterpret_cast<const uint4*>(base + brow[idx] + (b_keep_n ? k : k_begin));
     } else {
+      const int q = idx >> 3, j = idx & 7;
+      const int blk = tid + 256 * q;
+      if (C::BBLK >= 256 || blk < C::BBLK) {
+        const long k = l_k0 + (blk % CH) * 8 + j;
+        long row = n0 + (blk / CH) * 8;
+        row = row < g.Ndim ? row : n0;
+        const long kj = k < k_end ? k : k_end - 1;
+        rb[idx] = *reinterpret_cast<const uint4*>(lb_base + kj * g.b_ks + row);
+      }
+    }
+  };
+  auto write_a = [&](int stage, int idx) {   // idx: register (K-contiguous) or q*8 + block row (K-strided)
+    uint4* ta = smem + stage * C::STAGE_VEC;
+    if (A_KC) {
+      ta[(tid / CH + RP * idx) * C::PITCH + tid % CH] = sel4(a_keep != 0, ra[idx]);
+    } else {
+      const int q = idx >> 3, i = idx & 7;
+      const int blk = tid + 256 * q;
+      if (C::ABLK >= 256 || blk < C::ABLK) {
+        if (i == 0) {
 #pragma unroll
-      for (int q = 0; q < C::NBB; ++q) {
-        const int blk = tid + 256 * q;
-        if (C::BBLK >= 256 || blk < C::BBLK) {
-          if (b_keep != 0xffu) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) rb[q * 8 + j] = sel4((b_keep >> j) & 1u, rb[q * 8 + j]);
-          }
-#pragma unroll
-          for (int i = 0; i < 8; ++i) tb[((blk / CH) * 8 + i) * C::PITCH + blk % CH] = transpose_row(&rb[q * 8], i);
+          for (int j = 0; j < 8; ++j) ra[q * 8 + j] = sel4((a_keep >> j) & 1u, ra[q * 8 + j]);
         }
+        ta[((blk / CH) * 8 + i) * C::PITCH + blk % CH] = transpose_row(&ra[q * 8], i);
+      }
+    }
+  };
+  auto write_b = [&](int stage, int idx) {
+    uint4* tb = smem + stage * C::STAGE_VEC + C::A_VEC;
+    if (B_KC) {
+      tb[(tid / CH + RP * idx) * C::PITCH + tid % CH] = sel4(b_keep != 0, rb[idx]);
+    } else {
+      const int q = idx >> 3, i = idx & 7;
+      const int blk = tid + 256 * q;
+      if (C::BBLK >= 256 || blk < C::BBLK) {
+        if (i == 0) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) rb[q * 8 + j] = sel4((b_keep >> j) & 1u, rb[q * 8 + j]);
+        }
+        tb[((blk / CH) * 8 + i) * C::PITCH + blk % CH] = transpose_row(&rb[q * 8], i);
+      }
+    }
+  };
+  // piece p of the pipeline step "tile t+1 to LDS stage `stage`, tile t+2 into registers"
+  auto piece = [&](int p, int stage, bool do_write, bool do_load) {
+    if (p < NPA) {
+      if (A_KC) {
+        if (do_write) write_a(stage, p);
+        if (do_load) load_a(p);
+      } else {
+        const int q = p / 16, r = p % 16;
+        if (r < 8) { if (do_write) write_a(stage, q * 8 + r); }
+        else if (do_load) load_a(q * 8 + r - 8);
+      }
+    } else {
+      const int pb = p - NPA;
+      if (B_KC) {
+        if (do_write) write_b(stage, pb);
+        if (do_load) load_b(pb);
+      } else {
+        const int q = pb / 16, r = pb % 16;
+        if (r < 8) { if (do_write) write_b(stage, q * 8 + r); }
+        else if (do_load) load_b(q * 8 + r - 8);
       }
     }
   };
@@ -273,166 +298,179 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
     for (int j = 0; j < TN; ++j)
       fb[set][j] = __builtin_bit_cast(bf16x8, tb[(wn * (BN / 2) + j * 32 + l32) * C::PITCH + ks * 2 + lhalf]);
   };
-  auto mfmas = [&](int set) {
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int i = 0; i < TM; ++i) acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[j][i], 0, 0, 0);
-  };
 
   if (nsteps > 0) {
-    gload(0);
-    stash(0);
-    if (nsteps > 1) gload(1);
+    // prologue: tile 0 -> registers -> LDS stage 0, tile 1 -> registers
+    set_load_tile(0);
+#pragma unroll
+    for (int p = 0; p < NP; ++p) piece(p, 0, false, true);
+    a_keep = a_keep_n; b_keep = b_keep_n;
+    set_load_tile(nsteps > 1 ? 1 : 0);
+#pragma unroll
+    for (int p = 0; p < NP; ++p) piece(p, 0, true, true);
+    a_keep = a_keep_n; b_keep = b_keep_n;
     __syncthreads();
     read_frags(0, 0, 0);
-    constexpr int WRITE_KS = C::KSTEPS >= 4 ? 1 : 0;
+
+    constexpr int MF = TM * TN;                       // MFMAs per k-step
+    constexpr int SLOTS = (C::KSTEPS - 1) * MF;       // MFMA slots before the barrier of an iteration
     for (int t = 0; t < nsteps; ++t) {
+      // no branches in here: past the last K-tile the pipeline keeps running on clamped tiles whose
+      // results are never used (a spare LDS write, a repeated load)
       const int cur = t & 1;
+      set_load_tile(t + 2 < nsteps ? t + 2 : nsteps - 1);
 #pragma unroll
       for (int ks = 0; ks < C::KSTEPS; ++ks) {
         const int set = ks & 1;
         if (ks + 1 < C::KSTEPS) {
           read_frags(cur, ks + 1, set ^ 1);
-        } else if (t + 1 < nsteps) {
+        } else {
           read_frags(cur ^ 1, 0, set ^ 1);     // next K-tile, published by the barrier below
         }
-        if (ks == WRITE_KS) {
-          if (t + 1 < nsteps && !(g.dbg & 2)) stash(cur ^ 1);
-          if (t + 2 < nsteps && !(g.dbg & 1)) gload(t + 2);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int q = 0; q < MF; ++q) {
+          const int j = q / TM, i = q % TM;
+          acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[j][i], 0, 0, 0);
+          if (ks < C::KSTEPS - 1) {
+            const int slot = ks * MF + q;
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+              if (p * SLOTS / NP == slot) piece(p, cur ^ 1, true, true);
+          }
+          __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_sched_barrier(0);
-        if (!(g.dbg & 4)) mfmas(set);
-        __builtin_amdgcn_sched_barrier(0);
-        if (ks == C::KSTEPS - 2) __syncthreads();
+        if (ks == C::KSTEPS - 2) {
+          a_keep = a_keep_n; b_keep = b_keep_n;
+          __syncthreads();
+        }
       }
     }
   }
 
-  // ---- epilogue: lane holds row m = .. + l32 and, per register group gq, columns gq*8 + lhalf*4 + 0..3 ----
-  if (g.dbg & 8) return;
-  if (EPI == kEpiStore) {
+  // ---- epilogue ----
+  // The MFMA leaves each lane with 4-column runs of one row per register group, which would scatter 32-byte
+  // pieces over 32 rows per store.  Each wavefront therefore turns its sub-tile through a private LDS region,
+  // 32 rows at a time, and comes back with lanes laid along the columns: every global access below is a run of
+  // 256 to 512 contiguous bytes per row.
+  __syncthreads();                                   // the staging tiles are dead from here on
+  constexpr int ECOLS = TN * 32, EPITCH = ECOLS + 4; // floats per LDS row (pitch keeps the writes conflict-free)
+  float* ep = reinterpret_cast<float*>(smem) + wave * (32 * EPITCH);
+  const long m_base = m0 + wm * (BM / 2);
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const long m = m0 + wm * (BM / 2) + i * 32 + l32;
-      if (m >= m_end) continue;
+  for (int i = 0; i < TM; ++i) {
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-          const long n = n0 + wn * (BN / 2) + j * 32 + gq * 8 + lhalf * 4;
-          if (n >= g.Ndim) continue;
+      for (int gq = 0; gq < 4; ++gq)
+        *reinterpret_cast<float4*>(ep + l32 * EPITCH + j * 32 + gq * 8 + lhalf * 4) =
+            make_float4(acc[j][i][gq * 4], acc[j][i][gq * 4 + 1], acc[j][i][gq * 4 + 2], acc[j][i][gq * 4 + 3]);
+    if (EPI == kEpiStore) {
+      constexpr int CPR = ECOLS / 4, RPI = 64 / CPR;   // lanes per row, rows per access
+      const int c4 = lane % CPR;
+      const long n = n0 + wn * (BN / 2) + c4 * 4;
+#pragma unroll
+      for (int st = 0; st < 32 / RPI; ++st) {
+        const int row = st * RPI + lane / CPR;
+        const float4 v = *reinterpret_cast<const float4*>(ep + row * EPITCH + c4 * 4);
+        const long m = m_base + i * 32 + row;
+        if (m < m_end && n < g.Ndim) {
           const long ci = c_group + m * g.c_ms + n;
-          const float v0 = acc[j][i][gq * 4], v1 = acc[j][i][gq * 4 + 1], v2 = acc[j][i][gq * 4 + 2], v3 = acc[j][i][gq * 4 + 3];
           if (g.c_f32) {
             float4* c = reinterpret_cast<float4*>(reinterpret_cast<float*>(g.C[0]) + ci);
-            float4 o = make_float4(v0, v1, v2, v3);
+            float4 o = v;
             if (g.accumulate) { const float4 old = *c; o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w; }
             *c = o;
           } else {
-            *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.C[0]) + ci) = make_uint2(pack2(v0, v1), pack2(v2, v3));
+            *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.C[0]) + ci) = make_uint2(pack2(v.x, v.y), pack2(v.z, v.w));
           }
         }
-    }
-  } else if (EPI == kEpiSwiglu) {
+      }
+    } else if (EPI == kEpiSwiglu) {
+      // LDS columns [0, ECOLS/2) hold the gate projection, [ECOLS/2, ECOLS) the up projection of the same output columns
+      constexpr int CPR = ECOLS / 8, RPI = 64 / CPR;
+      const int c4 = lane % CPR;
+      const long n = n0 + wn * (BN / 4) + c4 * 4;
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const long m = m0 + wm * (BM / 2) + i * 32 + l32;
-      if (m >= m_end) continue;
-#pragma unroll
-      for (int j = 0; j < TN / 2; ++j)
-#pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-          const long n = n0 + wn * (BN / 4) + j * 32 + gq * 8 + lhalf * 4;
-          if (n >= g.Ndim) continue;
+      for (int st = 0; st < 32 / RPI; ++st) {
+        const int row = st * RPI + lane / CPR;
+        const float4 av = *reinterpret_cast<const float4*>(ep + row * EPITCH + c4 * 4);
+        const float4 bv = *reinterpret_cast<const float4*>(ep + row * EPITCH + ECOLS / 2 + c4 * 4);
+        const long m = m_base + i * 32 + row;
+        if (m < m_end && n < g.Ndim) {
           const long ci = m * g.c_ms + n;
-          float a[4], b[4], h[4];
+          const float a[4] = {av.x, av.y, av.z, av.w}, b[4] = {bv.x, bv.y, bv.z, bv.w};
+          float h[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            a[e] = acc[j][i][gq * 4 + e];
-            b[e] = acc[j + TN / 2][i][gq * 4 + e];
-            h[e] = a[e] * sigmoidf_(a[e]) * b[e];
-          }
-          *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.C[0]) + ci) = make_float4(a[0], a[1], a[2], a[3]);
-          *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.C[1]) + ci) = make_float4(b[0], b[1], b[2], b[3]);
+          for (int e = 0; e < 4; ++e) h[e] = a[e] * sigmoidf_(a[e]) * b[e];
+          *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.C[0]) + ci) = av;
+          *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.C[1]) + ci) = bv;
           *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.C[2]) + ci) = make_uint2(pack2(h[0], h[1]), pack2(h[2], h[3]));
         }
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const long m = m0 + wm * (BM / 2) + i * 32 + l32;
-      const bool min_ = m < m_end;
-      const float rs = min_ ? g.row_scale[m] : 0.f;
-      float dot = 0.f;
-      if (min_) {
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-          for (int gq = 0; gq < 4; ++gq) {
-            const long n = n0 + wn * (BN / 2) + j * 32 + gq * 8 + lhalf * 4;
-            if (n >= g.Ndim) continue;
-            const long ci = m * g.c_ms + n;
-            const float4 av = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(g.E[0]) + ci);
-            const float4 bv = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(g.E[1]) + ci);
-            const float a[4] = {av.x, av.y, av.z, av.w}, b[4] = {bv.x, bv.y, bv.z, bv.w};
-            float da[4], db[4], hg[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const float u = acc[j][i][gq * 4 + e];
-              const float sg = sigmoidf_(a[e]);
-              const float as = a[e] * sg;          // SiLU(a)
-              const float h = as * b[e];
-              dot = fmaf(u, h, dot);
-              const float dh = rs * u;
-              da[e] = dh * b[e] * (sg + as * (1.f - sg));
-              db[e] = dh * as;
-              hg[e] = rs * h;
-            }
-            *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.C[0]) + ci) = make_uint2(pack2(da[0], da[1]), pack2(da[2], da[3]));
-            *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.C[1]) + ci) = make_uint2(pack2(db[0], db[1]), pack2(db[2], db[3]));
-            *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.C[2]) + ci) = make_uint2(pack2(hg[0], hg[1]), pack2(hg[2], hg[3]));
-          }
       }
-      // the two half-waves hold the two column halves of the same row
-      dot += __shfl_xor(dot, 32, kWave);
-      if (min_ && lhalf == 0) g.rowdot[(long)(nt * 2 + wn) * g.rowdot_stride + m] = dot;
+    } else {
+      constexpr int CPR = ECOLS / 4, RPI = 64 / CPR;
+      const int c4 = lane % CPR;
+      const long n = n0 + wn * (BN / 2) + c4 * 4;
+#pragma unroll
+      for (int st = 0; st < 32 / RPI; ++st) {
+        const int row = st * RPI + lane / CPR;
+        const float4 uv = *reinterpret_cast<const float4*>(ep + row * EPITCH + c4 * 4);
+        const long m = m_base + i * 32 + row;
+        const bool in = m < m_end && n < g.Ndim;
+        float dot = 0.f;
+        if (in) {
+          const float rs = g.row_scale[m];
+          const long ci = m * g.c_ms + n;
+          const float4 av = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(g.E[0]) + ci);
+          const float4 bv = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(g.E[1]) + ci);
+          const float u[4] = {uv.x, uv.y, uv.z, uv.w}, a[4] = {av.x, av.y, av.z, av.w}, b[4] = {bv.x, bv.y, bv.z, bv.w};
+          float da[4], db[4], hg[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float sg = sigmoidf_(a[e]);
+            const float as = a[e] * sg;          // SiLU(a)
+            const float h = as * b[e];
+            dot = fmaf(u[e], h, dot);
+            const float dh = rs * u[e];
+            da[e] = dh * b[e] * (sg + as * (1.f - sg));
+            db[e] = dh * as;
+            hg[e] = rs * h;
+          }
+          *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.C[0]) + ci) = make_uint2(pack2(da[0], da[1]), pack2(da[2], da[3]));
+          *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.C[1]) + ci) = make_uint2(pack2(db[0], db[1]), pack2(db[2], db[3]));
+          *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.C[2]) + ci) = make_uint2(pack2(hg[0], hg[1]), pack2(hg[2], hg[3]));
+        }
+        // gate-gradient partial of this row over the wavefront's columns: the CPR lanes of a row sit side by side
+#pragma unroll
+        for (int o = CPR / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, kWave);
+        if (c4 == 0 && m < m_end) g.rowdot[(long)(nt * 2 + wn) * g.rowdot_stride + m] = dot;
+      }
     }
   }
 }
 
-// tile configurations: 256 x 128 x 32 with two blocks per CU (2 x 60 KB of LDS, 128 accumulators per lane),
-// or 256 x 256 x 64 with one block per CU (144 KB of LDS, 256 accumulators per lane)
-typedef Cfg<256, 128, 32, 2> Small;
-typedef Cfg<256, 256, 64, 1> Large;
-int g_tile = 0;   // 0: Small, 1: Large
-int g_dbg = 0;
+// one tile configuration: 256 x 256 x 64, one block per CU (144 KB of LDS, 256 accumulators per lane in AGPRs)
+typedef Cfg<256, 256, 64, 1> Tile;
 
-template <int MODE, int EPI, bool A_KC, bool B_KC, typename C>
-int launch_cfg(const GemmArgs& g, hipStream_t s) {
+template <int MODE, int EPI, bool A_KC, bool B_KC>
+int launch(const GemmArgs& g, hipStream_t s) {
+  typedef Tile C;
   const int bno = (EPI == kEpiSwiglu) ? C::BN / 2 : C::BN;
   const int gx = cdiv(g.Ndim, bno);
   long total = (MODE == kRaggedM) ? (long)g.max_tiles * gx : (long)g.n_groups * cdiv(g.Mdim, C::BM) * gx;
   if (total <= 0) return SPES_OK;
   total = (total + kXcds - 1) / kXcds * kXcds;
-  GemmArgs gg = g;
-  gg.dbg = g_dbg;
-  hipLaunchKernelGGL((gemm_mfma_kernel<MODE, EPI, A_KC, B_KC, C>), dim3((unsigned)total), dim3(256), 0, s, gg);
+  hipLaunchKernelGGL((gemm_mfma_kernel<MODE, EPI, A_KC, B_KC, C>), dim3((unsigned)total), dim3(256), 0, s, g);
   return hipGetLastError() == hipSuccess ? SPES_OK : SPES_EHIP;
-}
-
-template <int MODE, int EPI, bool A_KC, bool B_KC>
-int launch(const GemmArgs& g, hipStream_t s) {
-  if (g_tile == 1) return launch_cfg<MODE, EPI, A_KC, B_KC, Large>(g, s);
-  return launch_cfg<MODE, EPI, A_KC, B_KC, Small>(g, s);
 }
 
 }  // namespace
 
-void mfma_set_tile(int t) { g_tile = t & 0xff; g_dbg = t >> 8; }
-int mfma_row_tile() { return 256; }
+int mfma_row_tile() { return Tile::BM; }
 // number of gate-gradient partials per row that the kEpiDSwiglu epilogue writes for ndim columns
-int mfma_rowdot_parts(int ndim) { return 2 * cdiv(ndim, g_tile == 1 ? Large::BN : Small::BN); }
+int mfma_rowdot_parts(int ndim) { return 2 * cdiv(ndim, Tile::BN); }
+
 // bf16 operands only.  a_kcontig / b_kcontig: the contraction index is the fast memory axis of that operand.
 int launch_gemm_mfma(int mode, int epi, bool a_kcontig, bool b_kcontig, const GemmArgs& g, hipStream_t s) {
   if (mode == kRaggedM) {
