@@ -128,9 +128,7 @@ def main() -> int:
     ap.add_argument("--config", default="cfg2", help="workload name from spes_workloads.CONFIGS")
     ap.add_argument("--workload", default="layer", choices=["layer", "merge"],
                     help="layer: fwd+bwd of the MoE layer (the headline metric); merge: expert synchronisation sweep")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run a plain 1 GiB device-to-device copy (reference point for HBM byte counters)")
-    ap.add_argument("--cpu-sample", type=int, default=8192, help="tokens of the workload timed through the fp64 oracle (0: skip)")
+    ap.add_argument("--cpu-sample", type=int, default=16384, help="tokens of the workload timed through the fp64 oracle (0: skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -159,13 +157,19 @@ def main() -> int:
         L.fwd()
         L.bwd(0)
 
-    if args.copy_calibration:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)          # reads 1 GiB, writes 1 GiB
-        torch.cuda.synchronize()
-        del src, dst
+    # a plain 1 GiB device copy: reference point for the HBM byte counters and for what a stream achieves here
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(3):
+        dst.copy_(src)              # reads 1 GiB, writes 1 GiB
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 3 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
 
     for _ in range(args.warmup):
         step()
@@ -223,6 +227,8 @@ def main() -> int:
                      "unit": dom["unit"], "frac": dom["frac"], "traffic": None},
         "grouped_gemm_util": {"flop": gemm_flop, "ms": round(gemm_ms, 4), "achieved_tflops": round(gemm_flop / (gemm_ms * 1e-3) / 1e12, 2),
                               "peak_tflops": gemm_peak, "frac": round(gemm_flop / (gemm_ms * 1e-3) / 1e12 / gemm_peak, 4)},
+        "hbm_copy_reference": {"achieved": round(copy_gbs, 1), "unit": "GB/s", "frac": round(copy_gbs / PEAK_HBM_GBS, 4),
+                               "what": "plain 1 GiB device-to-device copy (read + write bytes) on this GPU"},
         "stages": stages,
     }
 

@@ -409,22 +409,34 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
         }
       }
     } else {
-      constexpr int CPR = ECOLS / 4, RPI = 64 / CPR;
+      constexpr int CPR = ECOLS / 4, RPI = 64 / CPR, STEPS = 32 / RPI, NB_ = 2, HALF = STEPS / NB_;
       const int c4 = lane % CPR;
       const long n = n0 + wn * (BN / 2) + c4 * 4;
 #pragma unroll
-      for (int st = 0; st < 32 / RPI; ++st) {
-        const int row = st * RPI + lane / CPR;
-        const float4 uv = *reinterpret_cast<const float4*>(ep + row * EPITCH + c4 * 4);
-        const long m = m_base + i * 32 + row;
-        const bool in = m < m_end && n < g.Ndim;
-        float dot = 0.f;
-        if (in) {
-          const float rs = g.row_scale[m];
-          const long ci = m * g.c_ms + n;
-          const float4 av = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(g.E[0]) + ci);
-          const float4 bv = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(g.E[1]) + ci);
-          const float u[4] = {uv.x, uv.y, uv.z, uv.w}, a[4] = {av.x, av.y, av.z, av.w}, b[4] = {bv.x, bv.y, bv.z, bv.w};
+      for (int hf = 0; hf < NB_; ++hf) {
+        // all saved projections of this half first: loads issued after a store wait for that store (one
+        // in-order counter covers both), so loads and stores are kept in separate batches
+        float4 av[HALF], bv[HALF];
+#pragma unroll
+        for (int q = 0; q < HALF; ++q) {
+          const int row = (hf * HALF + q) * RPI + lane / CPR;
+          const long m = m_base + i * 32 + row;
+          const long mc = m < m_end ? m : m_end - 1;
+          const long nc = n < g.Ndim ? n : 0;
+          const long ci = mc * g.c_ms + nc;
+          av[q] = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(g.E[0]) + ci);
+          bv[q] = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(g.E[1]) + ci);
+        }
+#pragma unroll
+        for (int q = 0; q < HALF; ++q) {
+          const int row = (hf * HALF + q) * RPI + lane / CPR;
+          const float4 uv = *reinterpret_cast<const float4*>(ep + row * EPITCH + c4 * 4);
+          const long m = m_base + i * 32 + row;
+          const bool in = m < m_end && n < g.Ndim;
+          float dot = 0.f;
+          const float rs = g.row_scale[m < m_end ? m : m_end - 1];
+          const float u[4] = {uv.x, uv.y, uv.z, uv.w}, a[4] = {av[q].x, av[q].y, av[q].z, av[q].w},
+                      b[4] = {bv[q].x, bv[q].y, bv[q].z, bv[q].w};
           float da[4], db[4], hg[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
@@ -437,14 +449,19 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
             db[e] = dh * as;
             hg[e] = rs * h;
           }
-          *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.C[0]) + ci) = make_uint2(pack2(da[0], da[1]), pack2(da[2], da[3]));
-          *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.C[1]) + ci) = make_uint2(pack2(db[0], db[1]), pack2(db[2], db[3]));
-          *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.C[2]) + ci) = make_uint2(pack2(hg[0], hg[1]), pack2(hg[2], hg[3]));
-        }
-        // gate-gradient partial of this row over the wavefront's columns: the CPR lanes of a row sit side by side
+          if (in) {
+            const long ci = m * g.c_ms + n;
+            *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.C[0]) + ci) = make_uint2(pack2(da[0], da[1]), pack2(da[2], da[3]));
+            *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.C[1]) + ci) = make_uint2(pack2(db[0], db[1]), pack2(db[2], db[3]));
+            *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.C[2]) + ci) = make_uint2(pack2(hg[0], hg[1]), pack2(hg[2], hg[3]));
+          } else {
+            dot = 0.f;
+          }
+          // gate-gradient partial of this row over the wavefront's columns: the CPR lanes of a row sit side by side
 #pragma unroll
-        for (int o = CPR / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, kWave);
-        if (c4 == 0 && m < m_end) g.rowdot[(long)(nt * 2 + wn) * g.rowdot_stride + m] = dot;
+          for (int o = CPR / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, kWave);
+          if (c4 == 0 && m < m_end) g.rowdot[(long)(nt * 2 + wn) * g.rowdot_stride + m] = dot;
+        }
       }
     }
   }
