@@ -363,7 +363,7 @@ SPES_API int spes_expert_warmup_merge(int32_t n_experts, int32_t dtype, int32_t 
     if (dtype == SPES_BF16 && M % 4 == 0) SPES_TRY(launch_gemm_mfma(kGroupedK, kEpiStore, true, true, g, s));
     else SPES_TRY(launch_gemm_simt(dtype, dtype, kGroupedK, kEpiStore, g, s));
   }
-  SPES_TRY(launch_sim_topk(static_cast<const float*>(scratch), ng, M, top_K, sim, nbr, s));
+  SPES_TRY(launch_sim_topk(static_cast<float*>(scratch), ng, M, top_K, sim, nbr, s));
   for (int m = 0; m < n_mats; ++m)
     SPES_TRY(launch_warmup_mix(dtype, M, elems[m], top_K, alpha, src[m], dst[m], nbr, s));
   return SPES_OK;

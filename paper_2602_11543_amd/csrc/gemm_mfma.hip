@@ -75,7 +75,8 @@ __device__ __forceinline__ uint4 transpose_row(const uint4* in, int i) {
   return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
-template <int MODE, int EPI, bool A_KC, bool B_KC, typename C>
+// A_KG: the K-strided operand A takes its k-rows through the index table a_rows (dy rows of an expert)
+template <int MODE, int EPI, bool A_KC, bool B_KC, bool A_KG, typename C>
 __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs g) {
   constexpr int BM = C::BM, BN = C::BN, BK = C::BK, TM = C::TM, TN = C::TN, CH = C::CH, RP = C::RP;
   __shared__ uint4 smem[2 * C::STAGE_VEC];
@@ -178,8 +179,20 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   const bf16_t* la_base = nullptr;
   const bf16_t* lb_base = nullptr;
   long l_k0 = 0;
+  int l_step = 0;
+  // gathered k-rows of the tile about to be loaded; fetched one tile ahead so that no load waits on an index
+  int kidx[A_KG ? 8 : 1];
+  auto load_kidx = [&](int step) {
+    if (A_KG) {
+      const int st = step < nsteps ? step : nsteps - 1;
+      const long k = k_begin + (long)(st % nk) * BK + (tid % CH) * 8;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) kidx[j] = g.a_rows[k + j < k_end ? k + j : k_end - 1];
+    }
+  };
   auto set_load_tile = [&](int step) {
     const int pass = step / nk;
+    l_step = step;
     l_k0 = k_begin + (long)(step - pass * nk) * BK;
     la_base = reinterpret_cast<const bf16_t*>(g.A[pass]);
     lb_base = reinterpret_cast<const bf16_t*>(g.B[(EPI == kEpiSwiglu) ? 0 : pass]) + (B_KC ? 0 : b_group);
@@ -208,9 +221,9 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
         const long k = l_k0 + (blk % CH) * 8 + j;
         long row = m0 + (blk / CH) * 8;
         row = row < m_end ? row : m0;
-        const long kj = k < k_end ? k : k_end - 1;
-        const long kr = g.a_rows ? (long)g.a_rows[kj] : kj;
+        const long kr = A_KG ? (long)kidx[j] : (k < k_end ? k : k_end - 1);
         ra[idx] = *reinterpret_cast<const uint4*>(la_base + kr * g.a_ks + row);
+        if (A_KG && j == 7) load_kidx(l_step + 1);
       }
     }
   };
@@ -301,6 +314,7 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
 
   if (nsteps > 0) {
     // prologue: tile 0 -> registers -> LDS stage 0, tile 1 -> registers
+    load_kidx(0);
     set_load_tile(0);
 #pragma unroll
     for (int p = 0; p < NP; ++p) piece(p, 0, false, true);
@@ -470,15 +484,16 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
 // one tile configuration: 256 x 256 x 64, one block per CU (144 KB of LDS, 256 accumulators per lane in AGPRs)
 typedef Cfg<256, 256, 64, 1> Tile;
 
-template <int MODE, int EPI, bool A_KC, bool B_KC>
+template <int MODE, int EPI, bool A_KC, bool B_KC, bool A_KG = false>
 int launch(const GemmArgs& g, hipStream_t s) {
   typedef Tile C;
+  static_assert(!A_KG || (!A_KC && C::NAB == 1), "k-row gather: K-strided A, one 8x8 block per thread");
   const int bno = (EPI == kEpiSwiglu) ? C::BN / 2 : C::BN;
   const int gx = cdiv(g.Ndim, bno);
   long total = (MODE == kRaggedM) ? (long)g.max_tiles * gx : (long)g.n_groups * cdiv(g.Mdim, C::BM) * gx;
   if (total <= 0) return SPES_OK;
   total = (total + kXcds - 1) / kXcds * kXcds;
-  hipLaunchKernelGGL((gemm_mfma_kernel<MODE, EPI, A_KC, B_KC, C>), dim3((unsigned)total), dim3(256), 0, s, g);
+  hipLaunchKernelGGL((gemm_mfma_kernel<MODE, EPI, A_KC, B_KC, A_KG, C>), dim3((unsigned)total), dim3(256), 0, s, g);
   return hipGetLastError() == hipSuccess ? SPES_OK : SPES_EHIP;
 }
 
@@ -500,7 +515,8 @@ int launch_gemm_mfma(int mode, int epi, bool a_kcontig, bool b_kcontig, const Ge
   }
   if (epi != kEpiStore) return SPES_EINVAL;
   if (a_kcontig && b_kcontig) return launch<kGroupedK, kEpiStore, true, true>(g, s);
-  if (!a_kcontig && !b_kcontig) return launch<kGroupedK, kEpiStore, false, false>(g, s);
+  if (!a_kcontig && !b_kcontig)
+    return g.a_rows ? launch<kGroupedK, kEpiStore, false, false, true>(g, s) : launch<kGroupedK, kEpiStore, false, false>(g, s);
   return SPES_EINVAL;
 }
 

@@ -29,7 +29,7 @@ int launch_reduce_partials(const float* partial, int n_partial, long n, float* o
 struct MergeSrc;
 int launch_sync_merge(int dtype, int n_experts, long elems, int n_nodes, const void* const* node_store, const int* slot,
                       const float* node_weight, void* dst, int* trainer_count, hipStream_t s);
-int launch_sim_topk(const float* partial, int n_partial, int M, int K, float* sim, int* nbr, hipStream_t s);
+int launch_sim_topk(float* partial, int n_partial, int M, int K, float* sim, int* nbr, hipStream_t s);
 int launch_warmup_mix(int dtype, int M, long elems, int K, float alpha, const void* src, void* dst, const int* nbr, hipStream_t s);
 
 }  // namespace spes

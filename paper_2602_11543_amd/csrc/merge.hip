@@ -60,16 +60,21 @@ __global__ void write_counts_kernel(const CountTable tb, int* __restrict__ train
   if (i < tb.n) trainer_count[tb.base + i] = tb.c[i];
 }
 
-// Sum the Gram partials in a fixed order, normalise to cosines, pick each row's top-K peers.
-__global__ __launch_bounds__(256) void sim_topk_kernel(const float* __restrict__ partial, int n_partial, int M, int K,
+// Sum the Gram partials in a fixed order: entry i of the result lands in partial 0.
+__global__ __launch_bounds__(64) void gram_reduce_kernel(float* __restrict__ partial, int n_partial, int n) {
+  const int i = blockIdx.x * 64 + threadIdx.x;
+  if (i >= n) return;
+  float acc = 0.f;
+  for (int p = 0; p < n_partial; ++p) acc += partial[(long)p * n + i];
+  partial[i] = acc;
+}
+
+// Normalise the Gram matrix to cosines and pick each row's top-K peers.
+__global__ __launch_bounds__(256) void sim_topk_kernel(const float* __restrict__ gram, int M, int K,
                                                        float* __restrict__ sim, int* __restrict__ nbr) {
   __shared__ float G[kMaxExperts][kMaxExperts + 1];
   const int tid = threadIdx.x;
-  for (int i = tid; i < M * M; i += 256) {
-    float acc = 0.f;
-    for (int p = 0; p < n_partial; ++p) acc += partial[(long)p * M * M + i];
-    G[i / M][i % M] = acc;
-  }
+  for (int i = tid; i < M * M; i += 256) G[i / M][i % M] = gram[i];
   __syncthreads();
   const int lane = tid & 63, w = tid >> 6;
   for (int j = w; j < M; j += 4) {
@@ -185,8 +190,9 @@ int launch_sync_merge(int dtype, int n_experts, long elems, int n_nodes, const v
   return SPES_OK;
 }
 
-int launch_sim_topk(const float* partial, int n_partial, int M, int K, float* sim, int* nbr, hipStream_t s) {
-  hipLaunchKernelGGL(sim_topk_kernel, dim3(1), dim3(256), 0, s, partial, n_partial, M, K, sim, nbr);
+int launch_sim_topk(float* partial, int n_partial, int M, int K, float* sim, int* nbr, hipStream_t s) {
+  hipLaunchKernelGGL(gram_reduce_kernel, dim3(cdiv((long)M * M, 64)), dim3(64), 0, s, partial, n_partial, M * M);
+  hipLaunchKernelGGL(sim_topk_kernel, dim3(1), dim3(256), 0, s, partial, M, K, sim, nbr);
   return ok();
 }
 
