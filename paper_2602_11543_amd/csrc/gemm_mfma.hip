@@ -27,6 +27,9 @@
 // assigned to the eight XCDs round-robin) gets one contiguous range of tiles: tiles
 // that share an expert's weight panel or a row panel meet in the same L2.
 #include "gemm.h"
+#ifndef SPES_EXP
+#define SPES_EXP 0
+#endif
 
 namespace spes {
 namespace {
@@ -60,7 +63,7 @@ __device__ __forceinline__ uint4 sel4(bool keep, const uint4& v) {
   const uint32_t m = keep ? 0xffffffffu : 0u;
   return make_uint4(v.x & m, v.y & m, v.z & m, v.w & m);
 }
-__device__ __forceinline__ uint32_t pack2(float a, float b) { return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16); }
+__device__ __forceinline__ uint32_t pack2(float a, float b) { return pack_bf16x2(a, b); }
 
 // out row i of an 8x8 block gets k_0..k_7 of row i; in[j] holds rows 0..7 at k_j
 __device__ __forceinline__ uint4 transpose_row(const uint4* in, int i) {
@@ -336,11 +339,13 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
 #pragma unroll
       for (int ks = 0; ks < C::KSTEPS; ++ks) {
         const int set = ks & 1;
+#if !(SPES_EXP & 8)
         if (ks + 1 < C::KSTEPS) {
           read_frags(cur, ks + 1, set ^ 1);
         } else {
           read_frags(cur ^ 1, 0, set ^ 1);     // next K-tile, published by the barrier below
         }
+#endif
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int q = 0; q < MF; ++q) {
@@ -350,13 +355,15 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
             const int slot = ks * MF + q;
 #pragma unroll
             for (int p = 0; p < NP; ++p)
-              if (p * SLOTS / NP == slot) piece(p, cur ^ 1, true, true);
+              if (p * SLOTS / NP == slot) piece(p, cur ^ 1, !(SPES_EXP & 2), !(SPES_EXP & 4));
           }
           __builtin_amdgcn_sched_barrier(0);
         }
         if (ks == C::KSTEPS - 2) {
           a_keep = a_keep_n; b_keep = b_keep_n;
+#if !(SPES_EXP & 1)
           __syncthreads();
+#endif
         }
       }
     }
