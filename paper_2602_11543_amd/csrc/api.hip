@@ -12,7 +12,7 @@ constexpr int kRouterSplit = 64;   // chunks of the token axis in the router wei
 
 struct Layout {
   spes_moe_ctx_layout pub;
-  size_t block_counts, tab_simt, tab_mfma, row_token, row_gate, dgate_part, da, db, hg, dxp, wr_part;
+  size_t block_counts, tab_simt, tab_mfma, row_token, row_gate, dgate_part, da, db, hg, dxp, wr_part, dlogits_bf, dxr;
   int max_tiles, max_tiles_mfma, max_col_tiles;
 };
 
@@ -67,6 +67,8 @@ Layout make_layout(const spes_moe_shape* s) {
   L.hg = take(R * f * es);
   L.dxp = take(R * d * es);
   L.wr_part = take((size_t)kRouterSplit * M * d * 4);
+  L.dlogits_bf = take(T * M * 2);
+  L.dxr = take(T * d * es);
   L.pub.total = off;
   return L;
 }
@@ -228,6 +230,8 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
   // through the SwiGLU, da and db of the gate-scaled upstream gradient
   const long R = (long)T * k;
   const int n_part = dt == SPES_BF16 ? mfma_rowdot_parts(f) : cdiv(f, simt_col_tile());
+  // bf16 storage: the two router contractions run on the matrix cores from a bf16 copy of dlogits
+  const bool router_mfma = dt == SPES_BF16 && M % 8 == 0;
   prof_begin(1, s);
   {
     GemmArgs g = blank();
@@ -244,7 +248,7 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
   prof_mark(1, "gemm_dgrad_down_dswiglu", s);
   SPES_TRY(launch_gating_bwd(at<float>(ctx, L.pub.logits), at<float>(ctx, L.pub.lse), idx, gate, at<float>(ctx, L.dgate_part),
                              n_part, R, inv, at<float>(ctx, L.pub.dgate), T, M, k, shape->renorm_topk,
-                             at<float>(ctx, L.pub.dlogits), s));
+                             at<float>(ctx, L.pub.dlogits), router_mfma ? at<bf16_t>(ctx, L.dlogits_bf) : nullptr, s));
   prof_mark(1, "gating_bwd", s);
   // dxp = da W_g + db W_u
   {
@@ -281,20 +285,37 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
     SPES_TRY(expert_gemm(dt, kGroupedK, kEpiStore, false, false, g, s));
     prof_mark(1, "wgrad_up", s);
   }
-  // dW_r[M,d] = dlogits^T x
+  // dW_r[M,d] = dlogits^T x; the token axis is cut into chunks whose partial products are then added in a fixed order
   {
     GemmArgs g = blank();
-    g.A[0] = at<float>(ctx, L.pub.dlogits); g.a_ms = 1; g.a_ks = M;
+    g.a_ms = 1; g.a_ks = M;
     g.B[0] = x; g.b_ns = 1; g.b_ks = d;
-    // the token axis is cut into chunks whose partial products are then added in a fixed order
-    g.Kdim = T; g.kchunk = cdiv(T, kRouterSplit); g.n_groups = cdiv(T, g.kchunk); g.Mdim = M; g.Ndim = d;
+    g.Kdim = T; g.Mdim = M; g.Ndim = d;
     g.C[0] = at<float>(ctx, L.wr_part); g.c_ms = d; g.c_gs = (long)M * d; g.c_f32 = 1;
-    SPES_TRY(launch_gemm_simt(SPES_F32, dt, kGroupedK, kEpiStore, g, s));
+    if (router_mfma) {
+      g.A[0] = at<void>(ctx, L.dlogits_bf);
+      g.kchunk = (cdiv(T, kRouterSplit / 2) + 63) / 64 * 64; g.n_groups = cdiv(T, g.kchunk);
+      SPES_TRY(launch_gemm_mfma(kGroupedK, kEpiStore, false, false, g, s));
+    } else {
+      g.A[0] = at<float>(ctx, L.pub.dlogits);
+      g.kchunk = cdiv(T, kRouterSplit); g.n_groups = cdiv(T, g.kchunk);
+      SPES_TRY(launch_gemm_simt(SPES_F32, dt, kGroupedK, kEpiStore, g, s));
+    }
     SPES_TRY(launch_reduce_partials(at<float>(ctx, L.wr_part), g.n_groups, (long)M * d, d_w_router, accumulate, s));
   }
   prof_mark(1, "router_wgrad", s);
-  // dx = unpermuted sum of dxp + dlogits W_r
-  SPES_TRY(launch_dx_gather(dt, at<void>(ctx, L.dxp), inv, at<float>(ctx, L.pub.dlogits), w_router, dx, T, d, k, M, s));
+  // router part of the input gradient, dxr[T,d] = dlogits W_r, as its own small GEMM in bf16 mode
+  if (router_mfma) {
+    GemmArgs g = blank();
+    g.A[0] = at<void>(ctx, L.dlogits_bf); g.a_ms = M; g.a_ks = 1;
+    g.B[0] = w_router; g.b_ns = 1; g.b_ks = d;
+    g.Kdim = M; g.kchunk = (M + 63) / 64 * 64; g.Mdim = T; g.Ndim = d;
+    g.C[0] = at<void>(ctx, L.dxr); g.c_ms = d;
+    SPES_TRY(launch_gemm_mfma(kGroupedK, kEpiStore, true, false, g, s));
+  }
+  // dx = unpermuted sum of dxp + router part
+  SPES_TRY(launch_dx_gather(dt, at<void>(ctx, L.dxp), inv, at<float>(ctx, L.pub.dlogits), w_router,
+                            router_mfma ? at<void>(ctx, L.dxr) : nullptr, dx, T, d, k, M, s));
   prof_mark(1, "unpermute_sum_router_dgrad", s);
   return SPES_OK;
 }

@@ -522,6 +522,7 @@ int launch_gemm_mfma(int mode, int epi, bool a_kcontig, bool b_kcontig, const Ge
   }
   if (epi != kEpiStore) return SPES_EINVAL;
   if (a_kcontig && b_kcontig) return launch<kGroupedK, kEpiStore, true, true>(g, s);
+  if (a_kcontig && !b_kcontig) return launch<kGroupedK, kEpiStore, true, false>(g, s);
   if (!a_kcontig && !b_kcontig)
     return g.a_rows ? launch<kGroupedK, kEpiStore, false, false, true>(g, s) : launch<kGroupedK, kEpiStore, false, false>(g, s);
   return SPES_EINVAL;

@@ -14,13 +14,13 @@ int launch_routing_tables(const int* idx, const float* gate, int R, int M, int k
                           int* tab1, int max_tiles, hipStream_t s);
 int launch_gating_bwd(const float* logits, const float* lse, const int* idx, const float* gate, const float* dgate_part,
                       int n_part, long part_stride, const int* inv, float* dgate, int T, int M, int k, int renorm, float* dlogits,
-                      hipStream_t s);
+                      bf16_t* dlogits_bf, hipStream_t s);
 
 // movement.hip (dtype = spes_dtype of the storage type)
 int launch_permute(int dtype, const void* x, const int* inv, int k, void* xp, int T, int d, hipStream_t s);
 int launch_combine(int dtype, const void* yp, const int* inv, const float* gate, void* y, int T, int d, int k, hipStream_t s);
-int launch_dx_gather(int dtype, const void* dxp, const int* inv, const float* dlogits, const void* w_router, void* dx, int T,
-                     int d, int k, int M, hipStream_t s);
+int launch_dx_gather(int dtype, const void* dxp, const int* inv, const float* dlogits, const void* w_router, const void* dxr,
+                     void* dx, int T, int d, int k, int M, hipStream_t s);
 
 // out[i] (+)= sum_p partial[p*n + i], p ascending (movement.hip)
 int launch_reduce_partials(const float* partial, int n_partial, long n, float* out, int accumulate, hipStream_t s);

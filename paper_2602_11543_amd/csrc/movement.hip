@@ -72,11 +72,12 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ yp, 
   }
 }
 
-// dx[t,:] = sum_j dxp[inv[t*k+j], :] + sum_e dlogits[t,e] * w_router[e,:]; one block per token
+// dx[t,:] = sum_j dxp[inv[t*k+j], :] + router part; one block per token.  The router part is either the row
+// dxr[t,:] computed beforehand, or sum_e dlogits[t,e] * w_router[e,:] formed here.
 template <typename T>
 __global__ __launch_bounds__(256) void dx_gather_kernel(const T* __restrict__ dxp, const int* __restrict__ inv,
                                                         const float* __restrict__ dlogits, const T* __restrict__ w_router,
-                                                        T* __restrict__ dx, int d, int k, int M) {
+                                                        const T* __restrict__ dxr, T* __restrict__ dx, int d, int k, int M) {
   constexpr int N = Vec16<T>::N;
   __shared__ float dl[kMaxExperts];
   __shared__ int rows[kMaxExperts];
@@ -97,14 +98,23 @@ __global__ __launch_bounds__(256) void dx_gather_kernel(const T* __restrict__ dx
 #pragma unroll
       for (int i = 0; i < N; ++i) acc[i] += f[i];
     }
-    for (int e = 0; e < M; ++e) {
+    if (dxr != nullptr) {
       Vec16<T> q;
-      q.load(w_router + (long)e * d + c * N);
+      q.load(dxr + t * d + c * N);
       float f[N];
       q.unpack(f);
-      const float s = dl[e];
 #pragma unroll
-      for (int i = 0; i < N; ++i) acc[i] = fmaf(s, f[i], acc[i]);
+      for (int i = 0; i < N; ++i) acc[i] += f[i];
+    } else {
+      for (int e = 0; e < M; ++e) {
+        Vec16<T> q;
+        q.load(w_router + (long)e * d + c * N);
+        float f[N];
+        q.unpack(f);
+        const float s = dl[e];
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] = fmaf(s, f[i], acc[i]);
+      }
     }
     Vec16<T> o;
     o.pack(acc);
@@ -176,14 +186,14 @@ int launch_reduce_partials(const float* partial, int n_partial, long n, float* o
   return ok();
 }
 
-int launch_dx_gather(int dtype, const void* dxp, const int* inv, const float* dlogits, const void* w_router, void* dx, int T,
-                     int d, int k, int M, hipStream_t s) {
+int launch_dx_gather(int dtype, const void* dxp, const int* inv, const float* dlogits, const void* w_router, const void* dxr,
+                     void* dx, int T, int d, int k, int M, hipStream_t s) {
   if (dtype == SPES_F32)
     hipLaunchKernelGGL(dx_gather_kernel<float>, dim3(T), dim3(256), 0, s, (const float*)dxp, inv, dlogits,
-                       (const float*)w_router, (float*)dx, d, k, M);
+                       (const float*)w_router, (const float*)dxr, (float*)dx, d, k, M);
   else
     hipLaunchKernelGGL(dx_gather_kernel<bf16_t>, dim3(T), dim3(256), 0, s, (const bf16_t*)dxp, inv, dlogits,
-                       (const bf16_t*)w_router, (bf16_t*)dx, d, k, M);
+                       (const bf16_t*)w_router, (const bf16_t*)dxr, (bf16_t*)dx, d, k, M);
   return ok();
 }
 

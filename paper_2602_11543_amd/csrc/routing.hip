@@ -162,7 +162,8 @@ __global__ __launch_bounds__(256) void gating_bwd_kernel(const float* __restrict
                                                          const int* __restrict__ topk_idx, const float* __restrict__ topk_gate,
                                                          const float* __restrict__ dgate_part, int n_part, long part_stride,
                                                          const int* __restrict__ inv, float* __restrict__ dgate, int T, int M,
-                                                         int k, int renorm, float* __restrict__ dlogits) {
+                                                         int k, int renorm, float* __restrict__ dlogits,
+                                                         bf16_t* __restrict__ dlogits_bf) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= T) return;
@@ -196,7 +197,10 @@ __global__ __launch_bounds__(256) void gating_bwd_kernel(const float* __restrict
     const float dot = wave_sum(dp * p);
     out = p * (dp - dot);
   }
-  if (lane < M) dlogits[(long)t * M + lane] = out;
+  if (lane < M) {
+    dlogits[(long)t * M + lane] = out;
+    if (dlogits_bf != nullptr) dlogits_bf[(long)t * M + lane] = f32_to_bf16(out);
+  }
 }
 
 }  // namespace
@@ -223,9 +227,9 @@ int launch_routing_tables(const int* idx, const float* gate, int R, int M, int k
 
 int launch_gating_bwd(const float* logits, const float* lse, const int* idx, const float* gate, const float* dgate_part,
                       int n_part, long part_stride, const int* inv, float* dgate, int T, int M, int k, int renorm, float* dlogits,
-                      hipStream_t s) {
+                      bf16_t* dlogits_bf, hipStream_t s) {
   hipLaunchKernelGGL(gating_bwd_kernel, dim3(cdiv(T, 4)), dim3(256), 0, s, logits, lse, idx, gate, dgate_part, n_part, part_stride,
-                     inv, dgate, T, M, k, renorm, dlogits);
+                     inv, dgate, T, M, k, renorm, dlogits, dlogits_bf);
   return hipGetLastError() == hipSuccess ? SPES_OK : SPES_EHIP;
 }
 
