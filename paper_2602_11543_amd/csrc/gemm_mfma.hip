@@ -92,10 +92,18 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   const int gx = cdiv(g.Ndim, BNO);
   long total;
   if (MODE == kRaggedM) total = (long)(*g.n_tiles) * gx; else total = (long)g.n_groups * cdiv(g.Mdim, BM) * gx;
-  const long per_xcd = (total + kXcds - 1) / kXcds;
-  const long slot = blockIdx.x / kXcds;
-  const long logical = (long)(blockIdx.x % kXcds) * per_xcd + slot;
-  if (slot >= per_xcd || logical >= total) return;
+  long logical;
+  if (MODE == kGroupedK && g.offset != nullptr) {
+    // ragged contraction lengths: tiles are taken in block order (round-robin over the XCDs) and the groups are
+    // visited longest first, so the long tiles start early and the short ones fill in behind them
+    logical = blockIdx.x;
+    if (logical >= total) return;
+  } else {
+    const long per_xcd = (total + kXcds - 1) / kXcds;
+    const long slot = blockIdx.x / kXcds;
+    logical = (long)(blockIdx.x % kXcds) * per_xcd + slot;
+    if (slot >= per_xcd || logical >= total) return;
+  }
   const int nt = (int)(logical % gx);
   const long mt_all = logical / gx;
 
@@ -108,10 +116,20 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
     b_group = (long)e * g.b_gs;
   } else {
     const int my = cdiv(g.Mdim, BM);
-    const int grp = (int)(mt_all / my);
+    int grp = (int)(mt_all / my);
     m0 = (mt_all % my) * BM;
     m_end = min((long)g.Mdim, m0 + BM);
     if (g.offset != nullptr) {
+      // grp counts positions in descending order of length; find the group that holds this position
+      // (lane j < n_groups owns group j; ties go to the lower group, so the order is a permutation)
+      const int mine = lane < g.n_groups ? g.offset[g.group_expert[lane] + 1] - g.offset[g.group_expert[lane]] : -1;
+      int rank = 0;
+      for (int j = 0; j < g.n_groups; ++j) {
+        const int other = __shfl(mine, j, kWave);
+        rank += (other > mine || (other == mine && j < lane)) ? 1 : 0;
+      }
+      const unsigned long long hit = __ballot(lane < g.n_groups && rank == grp);
+      grp = __ffsll((long long)hit) - 1;
       const int e = g.group_expert[grp];
       k_begin = g.offset[e]; k_end = g.offset[e + 1];
     } else {
