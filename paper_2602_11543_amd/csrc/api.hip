@@ -8,6 +8,7 @@ using namespace spes;
 
 namespace {
 
+constexpr int kLogitSplit = 4;    // chunks of d_model in the router GEMM on the matrix cores
 constexpr int kRouterSplit = 64;   // chunks of the token axis in the router weight gradient
 
 struct Layout {
@@ -41,7 +42,7 @@ Layout make_layout(const spes_moe_shape* s) {
   L.max_tiles_mfma = (int)(R / 256 + M + 1);
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += round_up(bytes, 256); return o; };
-  L.pub.logits = take(T * M * 4);
+  L.pub.logits = take(kLogitSplit * T * M * 4);   // partial score matrices; the first one ends up holding the scores
   L.pub.lse = take(T * 4);
   L.pub.topk_idx = take(R * 4);
   L.pub.topk_gate = take(R * 4);
@@ -155,6 +156,7 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
   const long R = (long)T * k;
 
   prof_begin(0, s);
+  int logit_parts = 1;
   // router scores: logits[T,M] = x W_r^T
   {
     GemmArgs g = blank();
@@ -162,12 +164,18 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
     g.B[0] = w_router; g.b_ns = d; g.b_ks = 1;
     g.Kdim = d; g.kchunk = d; g.Mdim = T; g.Ndim = M;
     g.C[0] = at<float>(ctx, L.pub.logits); g.c_ms = M; g.c_f32 = 1;
-    // the matrix-core epilogue stores four columns at a time
-    if (dt == SPES_BF16 && M % 4 == 0) SPES_TRY(launch_gemm_mfma(kGroupedK, kEpiStore, true, true, g, s));
-    else SPES_TRY(launch_gemm_simt(dt, dt, kGroupedK, kEpiStore, g, s));
+    // the matrix-core epilogue stores four columns at a time; with only M <= 64 output columns the row tiles alone
+    // would occupy a quarter of the CUs, so d_model is cut into partial products that the gating kernel adds up
+    if (dt == SPES_BF16 && M % 4 == 0) {
+      g.kchunk = (cdiv(d, kLogitSplit) + 63) / 64 * 64; g.n_groups = cdiv(d, g.kchunk); g.c_gs = (long)T * M;
+      logit_parts = g.n_groups;
+      SPES_TRY(launch_gemm_mfma(kGroupedK, kEpiStore, true, true, g, s));
+    } else {
+      SPES_TRY(launch_gemm_simt(dt, dt, kGroupedK, kEpiStore, g, s));
+    }
   }
   prof_mark(0, "router_gemm", s);
-  SPES_TRY(launch_topk_gate(at<float>(ctx, L.pub.logits), router_bias, T, M, k, shape->renorm_topk, topk_idx, topk_gate,
+  SPES_TRY(launch_topk_gate(at<float>(ctx, L.pub.logits), logit_parts, router_bias, T, M, k, shape->renorm_topk, topk_idx, topk_gate,
                             at<int>(ctx, L.pub.topk_idx), at<float>(ctx, L.pub.topk_gate), at<float>(ctx, L.pub.lse), s));
   prof_mark(0, "softmax_topk", s);
   SPES_TRY(launch_routing_tables(topk_idx, topk_gate, (int)R, M, k, at<int>(ctx, L.block_counts), expert_count,

@@ -7,8 +7,8 @@ namespace spes {
 
 // routing.hip
 int routing_blocks(int R);
-int launch_topk_gate(float* logits, const float* bias, int T, int M, int k, int renorm, int* idx, float* gate, int* idx_copy,
-                     float* gate_copy, float* lse, hipStream_t s);
+int launch_topk_gate(float* logits, int n_part, const float* bias, int T, int M, int k, int renorm, int* idx, float* gate,
+                     int* idx_copy, float* gate_copy, float* lse, hipStream_t s);
 int launch_routing_tables(const int* idx, const float* gate, int R, int M, int k, int* block_counts, int* expert_count,
                           int* offset, int* perm, int* inv, int* row_token, float* row_gate, int bm0, int* tab0, int bm1,
                           int* tab1, int max_tiles, hipStream_t s);

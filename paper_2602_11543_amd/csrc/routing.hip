@@ -8,7 +8,10 @@ namespace spes {
 namespace {
 
 // One wavefront per token, one router score per lane.
-__global__ __launch_bounds__(256) void topk_gate_kernel(float* __restrict__ logits, const float* __restrict__ bias,
+// logits holds n_part partial score matrices (the router contraction is cut along d_model); their sum plus the
+// bias is written back to the first one.
+__global__ __launch_bounds__(256) void topk_gate_kernel(float* __restrict__ logits, int n_part, long part_stride,
+                                                        const float* __restrict__ bias,
                                                         int T, int M, int k, int renorm, int* __restrict__ topk_idx,
                                                         float* __restrict__ topk_gate, int* __restrict__ idx_copy,
                                                         float* __restrict__ gate_copy, float* __restrict__ lse) {
@@ -18,10 +21,9 @@ __global__ __launch_bounds__(256) void topk_gate_kernel(float* __restrict__ logi
   float s = -INFINITY;
   if (lane < M) {
     s = logits[(long)t * M + lane];
-    if (bias != nullptr) {
-      s += bias[lane];
-      logits[(long)t * M + lane] = s;   // the backward recomputes probabilities from the biased score
-    }
+    for (int p = 1; p < n_part; ++p) s += logits[p * part_stride + (long)t * M + lane];
+    if (bias != nullptr) s += bias[lane];
+    if (bias != nullptr || n_part > 1) logits[(long)t * M + lane] = s;   // the backward recomputes probabilities from this score
   }
   const float mx = wave_max(s);
   const float ex = (lane < M) ? expf(s - mx) : 0.f;
@@ -84,10 +86,23 @@ __global__ __launch_bounds__(64) void scan_kernel(int* __restrict__ block_counts
                                                   int* __restrict__ tab1, int max_tiles) {
   const int e = threadIdx.x;
   int total = 0;
+#pragma unroll 8
   for (int b = 0; b < nblk; ++b) total += block_counts[b * kMaxExperts + e];
   const int off = wave_exclusive_scan(total, e);
   int running = off;
-  for (int b = 0; b < nblk; ++b) {
+  // eight independent loads in flight per step: this single wavefront is latency-bound
+  int b = 0;
+  for (; b + 8 <= nblk; b += 8) {
+    int c[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) c[u] = block_counts[(b + u) * kMaxExperts + e];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      block_counts[(b + u) * kMaxExperts + e] = running;
+      running += c[u];
+    }
+  }
+  for (; b < nblk; ++b) {
     const int c = block_counts[b * kMaxExperts + e];
     block_counts[b * kMaxExperts + e] = running;
     running += c;
@@ -207,10 +222,10 @@ __global__ __launch_bounds__(256) void gating_bwd_kernel(const float* __restrict
 
 int routing_blocks(int R) { return cdiv(R, kRankChunk); }
 
-int launch_topk_gate(float* logits, const float* bias, int T, int M, int k, int renorm, int* idx, float* gate, int* idx_copy,
-                     float* gate_copy, float* lse, hipStream_t s) {
-  hipLaunchKernelGGL(topk_gate_kernel, dim3(cdiv(T, 4)), dim3(256), 0, s, logits, bias, T, M, k, renorm, idx, gate, idx_copy,
-                     gate_copy, lse);
+int launch_topk_gate(float* logits, int n_part, const float* bias, int T, int M, int k, int renorm, int* idx, float* gate,
+                     int* idx_copy, float* gate_copy, float* lse, hipStream_t s) {
+  hipLaunchKernelGGL(topk_gate_kernel, dim3(cdiv(T, 4)), dim3(256), 0, s, logits, n_part, (long)T * M, bias, T, M, k, renorm,
+                     idx, gate, idx_copy, gate_copy, lse);
   return hipGetLastError() == hipSuccess ? SPES_OK : SPES_EHIP;
 }
 
