@@ -36,3 +36,39 @@ def test_product_package_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text, f
+
+
+def _fake(addr):
+    return ctypes.c_void_p(addr)
+
+
+def test_argument_checks_run_before_any_launch():
+    """Bad arguments are rejected on the host: these calls never reach the GPU (none is needed to run them)."""
+    lib = ctypes.CDLL(S.library_path())
+    lib.spes_moe_fwd.restype = ctypes.c_int32
+    lib.spes_moe_bwd.restype = ctypes.c_int32
+    lib.spes_expert_merge.restype = ctypes.c_int32
+    lib.spes_expert_warmup_merge.restype = ctypes.c_int32
+    ok_shape = S.moe_shape(64, 64, 8, 64, 2, S.SPES_BF16, 0)
+    p = [_fake(0x10000 + 0x1000 * i) for i in range(12)]           # aligned, never dereferenced
+    fwd = lambda shape, ptrs: lib.spes_moe_fwd(ctypes.byref(shape), *ptrs, None)
+    assert fwd(S.moe_shape(64, 64, 8, 64, 9, 1, 0), p[:11]) == -1          # top_k > n_experts
+    assert fwd(S.moe_shape(64, 64, 8, 64, 2, 7, 0), p[:11]) == -1          # unknown dtype
+    assert fwd(S.moe_shape(64, 64, 128, 64, 2, 1, 0), p[:11]) == -2        # more than 64 experts
+    assert fwd(S.moe_shape(64, 60, 8, 64, 2, 1, 0), p[:11]) == -2          # d_model not a multiple of 8
+    nulls = list(p[:11]); nulls[5] = None
+    assert fwd(ok_shape, nulls) == -1                                       # null y
+    nulls = list(p[:11]); nulls[2] = None
+    odd = list(p[:11]); odd[0] = _fake(0x10008)
+    assert fwd(ok_shape, odd) == -3                                         # misaligned x (null bias is allowed)
+    mask = (ctypes.c_uint8 * 8)(1, 0, 0, 0, 0, 0, 0, 0)
+    bwd_args = [p[0], p[1], p[2], p[3], p[4], p[5], p[6], ctypes.cast(mask, ctypes.c_void_p), p[7], p[8], None, p[9], p[10]]
+    assert lib.spes_moe_bwd(ctypes.byref(ok_shape), *bwd_args, 0, None) == -1   # a trainable expert but no d_w_gate buffer
+    slot = (ctypes.c_int32 * 4)(0, -1, -1, 0)
+    stores = (ctypes.c_void_p * 2)(0x20000, 0x30000)
+    args = lambda elems, dtype: (2, ctypes.c_int64(elems), dtype, 2, ctypes.cast(stores, ctypes.c_void_p),
+                                 ctypes.cast(slot, ctypes.c_void_p), None, p[0], None, None)
+    assert lib.spes_expert_merge(*args(100, 1)) == -2                       # elems not a multiple of 8
+    assert lib.spes_expert_merge(*args(128, 5)) == -1                       # unknown dtype
+    assert lib.spes_expert_warmup_merge(8, 1, 8, ctypes.c_float(0.1), p[0], ctypes.c_int64(64), 0, None, None, None, None,
+                                        p[1], p[2], None) == -1            # top_K must be < n_experts
