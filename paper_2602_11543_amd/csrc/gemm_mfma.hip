@@ -11,11 +11,14 @@
 //   * MFMA fragments are double-buffered in registers: the reads of k-step s+1 are
 //     issued before the MFMAs of k-step s, and the first fragments of the next K-tile
 //     are read (after the block barrier) under the last MFMAs of the current one.
-// Both operands live in LDS as [row][k] with a row pitch of BK*2+16 bytes, which
-// spreads the fragment reads (16 rows x one 16-byte chunk) over all banks.
+// An operand whose contraction index is the fast memory axis lives in LDS as [row][k]
+// with a row pitch of BK*2+16 bytes, which spreads the fragment reads (16 rows x one
+// 16-byte chunk) over all banks.
 // An operand whose contraction index is the slow memory axis (the weights in the
-// input-gradient GEMMs, both operands of the weight-gradient GEMMs) is transposed in
-// registers (8x8 blocks, v_perm) on its way into LDS.
+// input-gradient GEMMs, both operands of the weight-gradient GEMMs) keeps its memory
+// order in LDS, [k][row] with a pitch of rows*2+64 bytes: it is loaded in 512-byte
+// runs along a k-row, and the MFMA fragments (eight consecutive k of one row per lane)
+// come out of LDS through the transposing read ds_read_b64_tr_b16, four k at a time.
 // Loads are unconditional: rows and k beyond the operand are clamped to valid
 // addresses, the k tail is zeroed by select, surplus rows are never stored.
 //
@@ -27,9 +30,6 @@
 // assigned to the eight XCDs round-robin) gets one contiguous range of tiles: tiles
 // that share an expert's weight panel or a row panel meet in the same L2.
 #include "gemm.h"
-#ifndef SPES_EXP
-#define SPES_EXP 0
-#endif
 
 namespace spes {
 namespace {
@@ -50,11 +50,14 @@ struct Cfg {
   static constexpr int NA = BM / RP, NB = BN / RP;          // staging registers (uint4) per thread, K-contiguous
   static constexpr int A_VEC = BM * PITCH, B_VEC = BN * PITCH;
   static constexpr int STAGE_VEC = A_VEC + B_VEC;
-  // K-strided staging: 8x8 blocks, (rows/8)*CH of them per tile, spread over the 256 threads
-  static constexpr int ABLK = BM / 8 * CH, BBLK = BN / 8 * CH;
-  static constexpr int NAB = ABLK >= 256 ? ABLK / 256 : 1, NBB = BBLK >= 256 ? BBLK / 256 : 1;
-  static constexpr int RA = NA > 8 * NAB ? NA : 8 * NAB;    // staging register counts covering both kinds
-  static constexpr int RB = NB > 8 * NBB ? NB : 8 * NBB;
+  // K-strided operand: [k][row] in LDS; a k-row of the tile is BM/8 (BN/8) chunks and 64 bytes of padding, so that
+  // the four k-rows one transposing read touches start 16 banks apart
+  static constexpr int KPA = BM / 8 + 4, KPB = BN / 8 + 4;  // k-row pitch in 16-byte units
+  static constexpr int KRA = 256 / (BM / 8), KRB = 256 / (BN / 8);   // k-rows staged per pass
+  static constexpr int NAS = BK / KRA, NBS = BK / KRB;      // staging registers per thread, K-strided
+  static constexpr int RA = NA > NAS ? NA : NAS;            // staging register counts covering both kinds
+  static constexpr int RB = NB > NBS ? NB : NBS;
+  static_assert(BK * KPA <= A_VEC && BK * KPB <= B_VEC, "the [k][row] layout must fit the operand's LDS region");
 };
 
 __device__ __forceinline__ uint4 zero4() { return make_uint4(0, 0, 0, 0); }
@@ -65,17 +68,14 @@ __device__ __forceinline__ uint4 sel4(bool keep, const uint4& v) {
 }
 __device__ __forceinline__ uint32_t pack2(float a, float b) { return pack_bf16x2(a, b); }
 
-// out row i of an 8x8 block gets k_0..k_7 of row i; in[j] holds rows 0..7 at k_j
-__device__ __forceinline__ uint4 transpose_row(const uint4* in, int i) {
-  uint32_t w[4];
-#pragma unroll
-  for (int m = 0; m < 4; ++m) {
-    const uint32_t lo = (i >> 1) == 0 ? in[2 * m].x : (i >> 1) == 1 ? in[2 * m].y : (i >> 1) == 2 ? in[2 * m].z : in[2 * m].w;
-    const uint32_t hi =
-        (i >> 1) == 0 ? in[2 * m + 1].x : (i >> 1) == 1 ? in[2 * m + 1].y : (i >> 1) == 2 ? in[2 * m + 1].z : in[2 * m + 1].w;
-    w[m] = (i & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-  }
-  return make_uint4(w[0], w[1], w[2], w[3]);
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+// Transposing LDS read.  Within each group of 16 lanes, lane s supplies the address of four consecutive 16-bit
+// elements (think of them as row s of a 16 x 4 matrix); lane i receives column i%4 of rows i/4, i/4+4, i/4+8, i/4+12.
+// With lane s pointing at [k0 + s/4][r0 + 4*(s%4)] of a [k][row] tile, lane i gets k0..k0+3 of row r0+i.
+__device__ __forceinline__ uint2 lds_read_tr(const bf16_t* p) {
+  const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
+  return __builtin_bit_cast(uint2, v);
 }
 
 // A_KG: the K-strided operand A takes its k-rows through the index table a_rows (dy rows of an expert)
@@ -187,13 +187,12 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   // The loads and LDS writes of one K-tile are cut into pieces that the main loop issues one at a time between
   // MFMAs: a wavefront that issues sixteen 1 KB loads (or writes) back to back sits behind the memory queues for
   // well over a thousand cycles with its matrix pipe idle, while one piece every few MFMAs is absorbed for free.
-  //   K-contiguous operand: piece i = write register i to LDS (tile t+1), then reload it (tile t+2).
-  //   K-strided operand:    pieces 0..7 = transpose + write row i of the 8x8 block, pieces 8..15 = reload k-row j.
+  // Piece i = write staging register i to LDS (tile t+1), then reload it (tile t+2).
   uint4 ra[C::RA], rb[C::RB];
-  unsigned a_keep = 0, b_keep = 0;       // k inside the contraction range, for the tile held in ra / rb (bit j; K-contiguous: all/none)
+  unsigned a_keep = 0, b_keep = 0;       // k inside the contraction range, for the tile held in ra / rb (K-strided: bit i for register i)
   unsigned a_keep_n = 0, b_keep_n = 0;   // the same for the tile being loaded
-  constexpr int NPA = A_KC ? C::NA : 16 * C::NAB;
-  constexpr int NPB = B_KC ? C::NB : 16 * C::NBB;
+  constexpr int NPA = A_KC ? C::NA : C::NAS;
+  constexpr int NPB = B_KC ? C::NB : C::NBS;
   constexpr int NP = NPA + NPB;
 
   // scalar coordinates of the K-tile being loaded
@@ -202,14 +201,22 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   long l_k0 = 0;
   int l_step = 0;
   // gathered k-rows of the tile about to be loaded; fetched one tile ahead so that no load waits on an index
-  int kidx[A_KG ? 8 : 1];
+  constexpr int ACH = BM / 8, BCH = BN / 8;     // 16-byte chunks per k-row of a K-strided tile
+  int kidx[A_KG ? C::NAS : 1];
   auto load_kidx = [&](int step) {
     if (A_KG) {
       const int st = step < nsteps ? step : nsteps - 1;
-      const long k = k_begin + (long)(st % nk) * BK + (tid % CH) * 8;
+      const long k = k_begin + (long)(st % nk) * BK + tid / ACH;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) kidx[j] = g.a_rows[k + j < k_end ? k + j : k_end - 1];
+      for (int j = 0; j < C::NAS; ++j) kidx[j] = g.a_rows[k + j * C::KRA < k_end ? k + j * C::KRA : k_end - 1];
     }
+  };
+  // registers 0..n-1 of a K-strided operand hold k-rows inside the contraction range
+  auto keep_bits = [&](long first_k, int rows_per_pass, int nreg) -> unsigned {
+    const long left = k_end - first_k;
+    long n = (left + rows_per_pass - 1) / rows_per_pass;
+    n = n < 0 ? 0 : n > nreg ? nreg : n;
+    return (1u << n) - 1u;
   };
   auto set_load_tile = [&](int step) {
     const int pass = step / nk;
@@ -220,32 +227,26 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
     if (A_KC) {
       a_keep_n = (l_k0 + (tid % CH) * 8 < k_end) ? 0xffu : 0u;
     } else {
-      const long left = k_end - (l_k0 + (tid % CH) * 8);
-      a_keep_n = left >= 8 ? 0xffu : left <= 0 ? 0u : ((1u << left) - 1u);
+      a_keep_n = keep_bits(l_k0 + tid / ACH, C::KRA, C::NAS);
     }
     if (B_KC) {
       b_keep_n = (l_k0 + (tid % CH) * 8 < k_end) ? 0xffu : 0u;
     } else {
-      const long left = k_end - (l_k0 + (tid % CH) * 8);
-      b_keep_n = left >= 8 ? 0xffu : left <= 0 ? 0u : ((1u << left) - 1u);
+      b_keep_n = keep_bits(l_k0 + tid / BCH, C::KRB, C::NBS);
     }
   };
 
-  auto load_a = [&](int idx) {   // idx: register (K-contiguous) or q*8+j (K-strided)
+  auto load_a = [&](int idx) {   // idx: staging register
     if (A_KC) {
       const long k = l_k0 + (tid % CH) * 8;
       ra[idx] = *reinterpret_cast<const uint4*>(la_base + arow[idx] + (a_keep_n ? k : k_begin));
     } else {
-      const int q = idx >> 3, j = idx & 7;
-      const int blk = tid + 256 * q;
-      if (C::ABLK >= 256 || blk < C::ABLK) {
-        const long k = l_k0 + (blk % CH) * 8 + j;
-        long row = m0 + (blk / CH) * 8;
-        row = row < m_end ? row : m0;
-        const long kr = A_KG ? (long)kidx[j] : (k < k_end ? k : k_end - 1);
-        ra[idx] = *reinterpret_cast<const uint4*>(la_base + kr * g.a_ks + row);
-        if (A_KG && j == 7) load_kidx(l_step + 1);
-      }
+      const long k = l_k0 + tid / ACH + idx * C::KRA;
+      long row = m0 + (tid % ACH) * 8;
+      row = row < m_end ? row : m0;
+      const long kr = A_KG ? (long)kidx[idx] : (k < k_end ? k : k_end - 1);
+      ra[idx] = *reinterpret_cast<const uint4*>(la_base + kr * g.a_ks + row);
+      if (A_KG && idx == C::NAS - 1) load_kidx(l_step + 1);
     }
   };
   auto load_b = [&](int idx) {
@@ -254,31 +255,19 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
       const bf16_t* base = (EPI == kEpiSwiglu && bsecond[idx]) ? reinterpret_cast<const bf16_t*>(g.B[1]) : lb_base;
       rb[idx] = *reinterpret_cast<const uint4*>(base + brow[idx] + (b_keep_n ? k : k_begin));
     } else {
-      const int q = idx >> 3, j = idx & 7;
-      const int blk = tid + 256 * q;
-      if (C::BBLK >= 256 || blk < C::BBLK) {
-        const long k = l_k0 + (blk % CH) * 8 + j;
-        long row = n0 + (blk / CH) * 8;
-        row = row < g.Ndim ? row : n0;
-        const long kj = k < k_end ? k : k_end - 1;
-        rb[idx] = *reinterpret_cast<const uint4*>(lb_base + kj * g.b_ks + row);
-      }
+      const long k = l_k0 + tid / BCH + idx * C::KRB;
+      long row = n0 + (tid % BCH) * 8;
+      row = row < g.Ndim ? row : n0;
+      const long kj = k < k_end ? k : k_end - 1;
+      rb[idx] = *reinterpret_cast<const uint4*>(lb_base + kj * g.b_ks + row);
     }
   };
-  auto write_a = [&](int stage, int idx) {   // idx: register (K-contiguous) or q*8 + block row (K-strided)
+  auto write_a = [&](int stage, int idx) {
     uint4* ta = smem + stage * C::STAGE_VEC;
     if (A_KC) {
       ta[(tid / CH + RP * idx) * C::PITCH + tid % CH] = sel4(a_keep != 0, ra[idx]);
     } else {
-      const int q = idx >> 3, i = idx & 7;
-      const int blk = tid + 256 * q;
-      if (C::ABLK >= 256 || blk < C::ABLK) {
-        if (i == 0) {
-#pragma unroll
-          for (int j = 0; j < 8; ++j) ra[q * 8 + j] = sel4((a_keep >> j) & 1u, ra[q * 8 + j]);
-        }
-        ta[((blk / CH) * 8 + i) * C::PITCH + blk % CH] = transpose_row(&ra[q * 8], i);
-      }
+      ta[(tid / ACH + idx * C::KRA) * C::KPA + tid % ACH] = sel4((a_keep >> idx) & 1u, ra[idx]);
     }
   };
   auto write_b = [&](int stage, int idx) {
@@ -286,51 +275,46 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
     if (B_KC) {
       tb[(tid / CH + RP * idx) * C::PITCH + tid % CH] = sel4(b_keep != 0, rb[idx]);
     } else {
-      const int q = idx >> 3, i = idx & 7;
-      const int blk = tid + 256 * q;
-      if (C::BBLK >= 256 || blk < C::BBLK) {
-        if (i == 0) {
-#pragma unroll
-          for (int j = 0; j < 8; ++j) rb[q * 8 + j] = sel4((b_keep >> j) & 1u, rb[q * 8 + j]);
-        }
-        tb[((blk / CH) * 8 + i) * C::PITCH + blk % CH] = transpose_row(&rb[q * 8], i);
-      }
+      tb[(tid / BCH + idx * C::KRB) * C::KPB + tid % BCH] = sel4((b_keep >> idx) & 1u, rb[idx]);
     }
   };
   // piece p of the pipeline step "tile t+1 to LDS stage `stage`, tile t+2 into registers"
   auto piece = [&](int p, int stage, bool do_write, bool do_load) {
     if (p < NPA) {
-      if (A_KC) {
-        if (do_write) write_a(stage, p);
-        if (do_load) load_a(p);
-      } else {
-        const int q = p / 16, r = p % 16;
-        if (r < 8) { if (do_write) write_a(stage, q * 8 + r); }
-        else if (do_load) load_a(q * 8 + r - 8);
-      }
+      if (do_write) write_a(stage, p);
+      if (do_load) load_a(p);
     } else {
-      const int pb = p - NPA;
-      if (B_KC) {
-        if (do_write) write_b(stage, pb);
-        if (do_load) load_b(pb);
-      } else {
-        const int q = pb / 16, r = pb % 16;
-        if (r < 8) { if (do_write) write_b(stage, q * 8 + r); }
-        else if (do_load) load_b(q * 8 + r - 8);
-      }
+      if (do_write) write_b(stage, p - NPA);
+      if (do_load) load_b(p - NPA);
     }
   };
 
   bf16x8 fa[2][TM], fb[2][TN];
+  const int tr_k = lhalf * 8 + (lane & 15) / 4;                  // k-row (within a k-step) this lane points the transposing read at
+  const int tr_r = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;      // row (within a 32-row MFMA tile) likewise
   auto read_frags = [&](int stage, int ks, int set) {
     const uint4* ta = smem + stage * C::STAGE_VEC;
     const uint4* tb = ta + C::A_VEC;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
-      fa[set][i] = __builtin_bit_cast(bf16x8, ta[(wm * (BM / 2) + i * 32 + l32) * C::PITCH + ks * 2 + lhalf]);
+    for (int i = 0; i < TM; ++i) {
+      if (A_KC) {
+        fa[set][i] = __builtin_bit_cast(bf16x8, ta[(wm * (BM / 2) + i * 32 + l32) * C::PITCH + ks * 2 + lhalf]);
+      } else {
+        const bf16_t* p = reinterpret_cast<const bf16_t*>(ta + (ks * 16 + tr_k) * C::KPA) + wm * (BM / 2) + i * 32 + tr_r;
+        const uint2 lo = lds_read_tr(p), hi = lds_read_tr(p + 4 * C::KPA * 8);
+        fa[set][i] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+      }
+    }
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
-      fb[set][j] = __builtin_bit_cast(bf16x8, tb[(wn * (BN / 2) + j * 32 + l32) * C::PITCH + ks * 2 + lhalf]);
+    for (int j = 0; j < TN; ++j) {
+      if (B_KC) {
+        fb[set][j] = __builtin_bit_cast(bf16x8, tb[(wn * (BN / 2) + j * 32 + l32) * C::PITCH + ks * 2 + lhalf]);
+      } else {
+        const bf16_t* p = reinterpret_cast<const bf16_t*>(tb + (ks * 16 + tr_k) * C::KPB) + wn * (BN / 2) + j * 32 + tr_r;
+        const uint2 lo = lds_read_tr(p), hi = lds_read_tr(p + 4 * C::KPB * 8);
+        fb[set][j] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+      }
+    }
   };
 
   if (nsteps > 0) {
@@ -357,13 +341,11 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
 #pragma unroll
       for (int ks = 0; ks < C::KSTEPS; ++ks) {
         const int set = ks & 1;
-#if !(SPES_EXP & 8)
         if (ks + 1 < C::KSTEPS) {
           read_frags(cur, ks + 1, set ^ 1);
         } else {
           read_frags(cur ^ 1, 0, set ^ 1);     // next K-tile, published by the barrier below
         }
-#endif
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int q = 0; q < MF; ++q) {
@@ -373,15 +355,13 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
             const int slot = ks * MF + q;
 #pragma unroll
             for (int p = 0; p < NP; ++p)
-              if (p * SLOTS / NP == slot) piece(p, cur ^ 1, !(SPES_EXP & 2), !(SPES_EXP & 4));
+              if (p * SLOTS / NP == slot) piece(p, cur ^ 1, true, true);
           }
           __builtin_amdgcn_sched_barrier(0);
         }
         if (ks == C::KSTEPS - 2) {
           a_keep = a_keep_n; b_keep = b_keep_n;
-#if !(SPES_EXP & 1)
           __syncthreads();
-#endif
         }
       }
     }
@@ -512,7 +492,7 @@ typedef Cfg<256, 256, 64, 1> Tile;
 template <int MODE, int EPI, bool A_KC, bool B_KC, bool A_KG = false>
 int launch(const GemmArgs& g, hipStream_t s) {
   typedef Tile C;
-  static_assert(!A_KG || (!A_KC && C::NAB == 1), "k-row gather: K-strided A, one 8x8 block per thread");
+  static_assert(!A_KG || !A_KC, "k-row gather: K-strided A only");
   const int bno = (EPI == kEpiSwiglu) ? C::BN / 2 : C::BN;
   const int gx = cdiv(g.Ndim, bno);
   long total = (MODE == kRaggedM) ? (long)g.max_tiles * gx : (long)g.n_groups * cdiv(g.Mdim, C::BM) * gx;
