@@ -376,6 +376,35 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   constexpr int ECOLS = TN * 32, EPITCH = ECOLS + 4; // floats per LDS row (pitch keeps the writes conflict-free)
   float* ep = reinterpret_cast<float*>(smem) + wave * (32 * EPITCH);
   const long m_base = m0 + wm * (BM / 2);
+  // dSwiGLU epilogue: lanes lie along the columns (DS_CPR lanes per row, four columns each); the saved fp32
+  // projections come in batches of half a 32-row slab
+  constexpr int DS_CPR = ECOLS / 4, DS_RPI = 64 / DS_CPR, DS_NB = 2, DS_HALF = 32 / DS_RPI / DS_NB;
+  const int ds_c4 = lane % DS_CPR;
+  const long ds_n = n0 + wn * (BN / 2) + ds_c4 * 4;
+  // addresses are a per-tile base (uniform) plus a 32-bit offset: one register per address instead of two
+  const long ds_tile = m0 * g.c_ms;
+  const int ds_rows = (int)(m_end - m0);                        // valid rows of the tile
+  const int ds_r0 = wm * (BM / 2) + lane / DS_CPR;
+  const bool ds_nin = ds_n < g.Ndim;
+  const unsigned ds_ncl = ds_nin ? (unsigned)ds_n : 0u;
+  const float* ds_a = reinterpret_cast<const float*>(g.E[0]) + ds_tile;
+  const float* ds_b = reinterpret_cast<const float*>(g.E[1]) + ds_tile;
+  bf16_t* ds_c0 = reinterpret_cast<bf16_t*>(g.C[0]) + ds_tile;
+  bf16_t* ds_c1 = reinterpret_cast<bf16_t*>(g.C[1]) + ds_tile;
+  bf16_t* ds_c2 = reinterpret_cast<bf16_t*>(g.C[2]) + ds_tile;
+  float4 av[EPI == kEpiDSwiglu ? DS_HALF : 1], bv[EPI == kEpiDSwiglu ? DS_HALF : 1];
+  auto load_ab = [&](int i, int hf) {
+    if (EPI == kEpiDSwiglu) {
+#pragma unroll
+      for (int q = 0; q < DS_HALF; ++q) {
+        const int rt = ds_r0 + i * 32 + (hf * DS_HALF + q) * DS_RPI;     // row within the tile
+        const unsigned ci = (unsigned)(rt < ds_rows ? rt : ds_rows - 1) * (unsigned)g.c_ms + ds_ncl;
+        av[q] = *reinterpret_cast<const float4*>(ds_a + ci);
+        bv[q] = *reinterpret_cast<const float4*>(ds_b + ci);
+      }
+    }
+  };
+  load_ab(0, 0);
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -428,35 +457,19 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
         }
       }
     } else {
-      constexpr int CPR = ECOLS / 4, RPI = 64 / CPR, STEPS = 32 / RPI, NB_ = 2, HALF = STEPS / NB_;
-      const int c4 = lane % CPR;
-      const long n = n0 + wn * (BN / 2) + c4 * 4;
 #pragma unroll
-      for (int hf = 0; hf < NB_; ++hf) {
-        // all saved projections of this half first: loads issued after a store wait for that store (one
-        // in-order counter covers both), so loads and stores are kept in separate batches
-        float4 av[HALF], bv[HALF];
+      for (int hf = 0; hf < DS_NB; ++hf) {
+        uint2 oa[DS_HALF], ob[DS_HALF], oh[DS_HALF];
+        float dots[DS_HALF];
 #pragma unroll
-        for (int q = 0; q < HALF; ++q) {
-          const int row = (hf * HALF + q) * RPI + lane / CPR;
-          const long m = m_base + i * 32 + row;
-          const long mc = m < m_end ? m : m_end - 1;
-          const long nc = n < g.Ndim ? n : 0;
-          const long ci = mc * g.c_ms + nc;
-          av[q] = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(g.E[0]) + ci);
-          bv[q] = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(g.E[1]) + ci);
-        }
-#pragma unroll
-        for (int q = 0; q < HALF; ++q) {
-          const int row = (hf * HALF + q) * RPI + lane / CPR;
-          const float4 uv = *reinterpret_cast<const float4*>(ep + row * EPITCH + c4 * 4);
-          const long m = m_base + i * 32 + row;
-          const bool in = m < m_end && n < g.Ndim;
-          float dot = 0.f;
-          const float rs = g.row_scale[m < m_end ? m : m_end - 1];
+        for (int q = 0; q < DS_HALF; ++q) {
+          const int row = (hf * DS_HALF + q) * DS_RPI + lane / DS_CPR;
+          const float4 uv = *reinterpret_cast<const float4*>(ep + row * EPITCH + ds_c4 * 4);
+          const int rt = ds_r0 + i * 32 + (hf * DS_HALF + q) * DS_RPI;
+          const float rs = g.row_scale[m0 + (rt < ds_rows ? rt : ds_rows - 1)];
           const float u[4] = {uv.x, uv.y, uv.z, uv.w}, a[4] = {av[q].x, av[q].y, av[q].z, av[q].w},
                       b[4] = {bv[q].x, bv[q].y, bv[q].z, bv[q].w};
-          float da[4], db[4], hg[4];
+          float da[4], db[4], hg[4], dot = 0.f;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const float sg = sigmoidf_(a[e]);
@@ -468,18 +481,32 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
             db[e] = dh * as;
             hg[e] = rs * h;
           }
-          if (in) {
-            const long ci = m * g.c_ms + n;
-            *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.C[0]) + ci) = make_uint2(pack2(da[0], da[1]), pack2(da[2], da[3]));
-            *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.C[1]) + ci) = make_uint2(pack2(db[0], db[1]), pack2(db[2], db[3]));
-            *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.C[2]) + ci) = make_uint2(pack2(hg[0], hg[1]), pack2(hg[2], hg[3]));
-          } else {
-            dot = 0.f;
-          }
+          oa[q] = make_uint2(pack2(da[0], da[1]), pack2(da[2], da[3]));
+          ob[q] = make_uint2(pack2(db[0], db[1]), pack2(db[2], db[3]));
+          oh[q] = make_uint2(pack2(hg[0], hg[1]), pack2(hg[2], hg[3]));
+          if (!(rt < ds_rows && ds_nin)) dot = 0.f;
           // gate-gradient partial of this row over the wavefront's columns: the CPR lanes of a row sit side by side
 #pragma unroll
-          for (int o = CPR / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, kWave);
-          if (c4 == 0 && m < m_end) g.rowdot[(long)(nt * 2 + wn) * g.rowdot_stride + m] = dot;
+          for (int o = DS_CPR / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, kWave);
+          dots[q] = dot;
+        }
+        // The saved projections of the next half-slab are requested before this one's results are stored: one
+        // in-order counter covers loads and stores, so a load issued after a store would wait for that store to
+        // be acknowledged, and every half-slab would pay a full load and a full store round trip in sequence.
+        __builtin_amdgcn_sched_barrier(0);
+        if (hf + 1 < DS_NB) load_ab(i, hf + 1);
+        else if (i + 1 < TM) load_ab(i + 1, 0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int q = 0; q < DS_HALF; ++q) {
+          const int rt = ds_r0 + i * 32 + (hf * DS_HALF + q) * DS_RPI;
+          if (rt < ds_rows && ds_nin) {
+            const unsigned ci = (unsigned)rt * (unsigned)g.c_ms + ds_ncl;
+            *reinterpret_cast<uint2*>(ds_c0 + ci) = oa[q];
+            *reinterpret_cast<uint2*>(ds_c1 + ci) = ob[q];
+            *reinterpret_cast<uint2*>(ds_c2 + ci) = oh[q];
+          }
+          if (ds_c4 == 0 && rt < ds_rows) g.rowdot[(long)(nt * 2 + wn) * g.rowdot_stride + m0 + rt] = dots[q];
         }
       }
     }
