@@ -372,7 +372,6 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   // pieces over 32 rows per store.  Each wavefront therefore turns its sub-tile through a private LDS region,
   // 32 rows at a time, and comes back with lanes laid along the columns: every global access below is a run of
   // 256 to 512 contiguous bytes per row.
-  __syncthreads();                                   // the staging tiles are dead from here on
   constexpr int ECOLS = TN * 32, EPITCH = ECOLS + 4; // floats per LDS row (pitch keeps the writes conflict-free)
   float* ep = reinterpret_cast<float*>(smem) + wave * (32 * EPITCH);
   const long m_base = m0 + wm * (BM / 2);
@@ -405,6 +404,7 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
     }
   };
   load_ab(0, 0);
+  __syncthreads();                                   // the staging tiles are dead from here on
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
