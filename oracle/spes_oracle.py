@@ -18,6 +18,8 @@ order of appearance):
 * sparse synchronisation (average / direct assignment)          -- Sec. 3.3, Eq. 4; App. A sync rules
 * expert-merging warm-up (cosine similarity, top-K, task
   arithmetic, all right-hand sides pre-merge)                   -- Sec. 3.3, Eq. 5-6; App. A merge step
+* router auxiliary losses: load-balancing loss and router
+  z-loss, with the coefficients of the implementation details   -- Sec. 3.3 "Training Losses"; App. B
 
 Every function takes numpy arrays of already-rounded inputs and up-converts them
 to float64; nothing is blocked, fused or reordered beyond "for each expert, the
@@ -178,8 +180,46 @@ def gating_backward(p, idx, gate, dgate, renorm):
     return p * (dp - (dp * p).sum(axis=1, keepdims=True))
 
 
-def moe_backward(fwd, dy, x, w_router, w_gate, w_up, w_down, renorm, wgrad_experts=None):
+def router_aux_losses(logits, idx):
+    """The two auxiliary router losses named in Sec. 3.3 "Training Losses" (the paper names them and cites their
+    sources; the formulas are the cited ones, written out).
+
+    load-balancing:  L_lb = M * sum_e f_e * P_e,  f_e = share of the T*k routed pairs that went to expert e,
+                     P_e = mean over tokens of the softmax probability of expert e;
+    router z-loss:   L_z  = mean over tokens of (log sum_e exp(logit_te))^2.
+    Returns (L_lb, L_z, f [M], P [M]).
+    """
+    s = _f64(logits)
+    T, M = s.shape
+    k = idx.shape[1]
+    f = np.zeros(M)
+    for e in range(M):
+        f[e] = np.count_nonzero(idx == e) / float(T * k)
+    P = softmax(s).mean(axis=0)
+    m = s.max(axis=1)
+    lse = m + np.log(np.exp(s - m[:, None]).sum(axis=1))
+    return float(M * (f * P).sum()), float((lse ** 2).mean()), f, P
+
+
+def router_aux_dlogits(logits, idx, lb_coef, z_coef, grad_scale=1.0):
+    """d/dlogits of grad_scale * (lb_coef * L_lb + z_coef * L_z).  The routed shares f_e are counts and carry no
+    gradient; L_lb reaches the logits through P_e only."""
+    s = _f64(logits)
+    T, M = s.shape
+    _, _, f, _ = router_aux_losses(s, idx)
+    p = softmax(s)
+    m = s.max(axis=1)
+    lse = m + np.log(np.exp(s - m[:, None]).sum(axis=1))
+    dP = lb_coef * M * f / T                                    # dL/dp_te, the same for every token
+    d_lb = p * (dP[None, :] - (p * dP[None, :]).sum(axis=1, keepdims=True))
+    d_z = z_coef * (2.0 / T) * lse[:, None] * p                 # d lse / d logit = p
+    return grad_scale * (d_lb + d_z)
+
+
+def moe_backward(fwd, dy, x, w_router, w_gate, w_up, w_down, renorm, wgrad_experts=None, extra_dlogits=None):
     """Backward of the layer given the forward record `fwd` (keep=True) and dy [T,d].
+    `extra_dlogits` [T,M], if given, is added to the gating gradient before it reaches the router
+    (the auxiliary router losses enter here).
 
     The selected index set is treated as constant.  Input gradients flow through
     every routed expert.  Weight gradients are returned per expert in dicts
@@ -212,6 +252,8 @@ def moe_backward(fwd, dy, x, w_router, w_gate, w_up, w_down, renorm, wgrad_exper
         if e in wgrad_experts:
             dwg[e], dwu[e], dwd[e] = dwg_e, dwu_e, dwd_e
     dlogits = gating_backward(fwd["p"], idx, g, dgate, renorm)
+    if extra_dlogits is not None:
+        dlogits = dlogits + _f64(extra_dlogits)
     d_w_router = dlogits.T @ x
     dx_experts = dx.copy()
     dx = dx + dlogits @ _f64(w_router)
