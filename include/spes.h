@@ -128,6 +128,27 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
                           float* d_w_router, float* d_w_gate, float* d_w_up, float* d_w_down,
                           int32_t accumulate, void* stream);
 
+/* Auxiliary router losses (Sec. 3.3 "Training Losses"; coefficients App. B: load-balancing
+ * 0.01, router z-loss 0.001).  The paper names the two losses and cites their sources; the
+ * formulas used are the cited ones:
+ *      L_lb = M * sum_e f_e * P_e     f_e = share of the T*k routed pairs sent to expert e,
+ *                                     P_e = mean over tokens of the softmax probability of e
+ *      L_z  = mean over tokens of (log sum_e exp(score_te))^2
+ * on the scores (router bias included) of the forward pass whose record is in ctx.
+ * Call it after spes_moe_fwd and before spes_moe_bwd on the same ctx.  It writes the two loss
+ * values and arms ctx so that the next spes_moe_bwd adds
+ *      grad_scale * (lb_coef * dL_lb/dscores + z_coef * dL_z/dscores)
+ * to the gating gradient before it reaches d_w_router and dx (f_e is a count and carries no
+ * gradient).  grad_scale is whatever factor the caller's total loss applies to this layer's
+ * auxiliary terms (1 for a plain sum, 1/n for n micro-batches, a loss scale).  The next
+ * spes_moe_fwd on the ctx disarms it; without this call spes_moe_bwd is unchanged.
+ *
+ *  ctx     DEVICE, as left by spes_moe_fwd for this shape
+ *  losses  DEVICE [2] f32 out: L_lb, L_z (unweighted)
+ */
+SPES_API int spes_moe_router_aux(const spes_moe_shape* shape, void* ctx, float lb_coef,
+                                 float z_coef, float grad_scale, float* losses, void* stream);
+
 /* Synchronisation of node-local expert copies (Sec. 3.3 Eq. 4; App. A sync rules),
  * for one parameter matrix of every expert.  Expert j becomes the weighted mean
  * of the copies held by the nodes that trained it,

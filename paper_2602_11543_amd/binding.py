@@ -49,6 +49,8 @@ def _load() -> ctypes.CDLL:
     lib.spes_moe_fwd.argtypes = [shp] + [vp] * 12
     lib.spes_moe_bwd.restype = i32
     lib.spes_moe_bwd.argtypes = [shp] + [vp] * 13 + [i32, vp]
+    lib.spes_moe_router_aux.restype = i32
+    lib.spes_moe_router_aux.argtypes = [shp, vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, vp, vp]
     lib.spes_expert_merge.restype = i32
     lib.spes_expert_merge.argtypes = [i32, i64, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.spes_warmup_scratch_bytes.restype = sz
@@ -127,6 +129,11 @@ def spes_moe_bwd(shape, dy, x, w_router, w_gate, w_up, w_down, ctx, trainable_ma
     _check(_lib.spes_moe_bwd(ctypes.byref(shape), _dev(dy), _dev(x), _dev(w_router), _dev(w_gate), _dev(w_up), _dev(w_down),
                              _dev(ctx), mask.ctypes.data_as(ctypes.c_void_p), _dev(dx), _dev(d_w_router), _dev(d_w_gate),
                              _dev(d_w_up), _dev(d_w_down), int(accumulate), _stream(stream)), "spes_moe_bwd")
+
+
+def spes_moe_router_aux(shape, ctx, lb_coef, z_coef, grad_scale, losses, stream=None) -> None:
+    _check(_lib.spes_moe_router_aux(ctypes.byref(shape), _dev(ctx), float(lb_coef), float(z_coef), float(grad_scale),
+                                    _dev(losses), _stream(stream)), "spes_moe_router_aux")
 
 
 def spes_expert_merge(n_experts, elems, dtype, node_store: Sequence[Optional[torch.Tensor]], slot, node_weight, dst,

@@ -13,7 +13,7 @@ constexpr int kRouterSplit = 64;   // chunks of the token axis in the router wei
 
 struct Layout {
   spes_moe_ctx_layout pub;
-  size_t block_counts, tab_simt, tab_mfma, row_token, row_gate, dgate_part, da, db, hg, dxp, wr_part, dlogits_bf, dxr;
+  size_t block_counts, tab_simt, tab_mfma, row_token, row_gate, dgate_part, da, db, hg, dxp, wr_part, dlogits_bf, dxr, aux, aux_part;
   int max_tiles, max_tiles_mfma, max_col_tiles;
 };
 
@@ -70,6 +70,8 @@ Layout make_layout(const spes_moe_shape* s) {
   L.wr_part = take((size_t)kRouterSplit * M * d * 4);
   L.dlogits_bf = take(T * M * 2);
   L.dxr = take(T * d * es);
+  L.aux = take((kMaxExperts + kAuxExtra) * 4);
+  L.aux_part = take((size_t)kAuxBlocks * (kMaxExperts + 1) * 4);
   L.pub.total = off;
   return L;
 }
@@ -181,7 +183,8 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
   SPES_TRY(launch_routing_tables(topk_idx, topk_gate, (int)R, M, k, at<int>(ctx, L.block_counts), expert_count,
                                  at<int>(ctx, L.pub.offset), at<int>(ctx, L.pub.perm), at<int>(ctx, L.pub.inv),
                                  at<int>(ctx, L.row_token), at<float>(ctx, L.row_gate), simt_row_tile(),
-                                 at<int>(ctx, L.tab_simt), mfma_row_tile(), at<int>(ctx, L.tab_mfma), L.max_tiles, s));
+                                 at<int>(ctx, L.tab_simt), mfma_row_tile(), at<int>(ctx, L.tab_mfma), L.max_tiles,
+                                 at<float>(ctx, L.aux), s));
   prof_mark(0, "hist_scan_rank", s);
   SPES_TRY(launch_permute(dt, x, at<int>(ctx, L.pub.inv), k, at<void>(ctx, L.pub.xp), T, d, s));
   prof_mark(0, "permute", s);
@@ -210,6 +213,18 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
   SPES_TRY(launch_combine(dt, at<void>(ctx, L.pub.yp), at<int>(ctx, L.pub.inv), topk_gate, y, T, d, k, s));
   prof_mark(0, "combine", s);
   return SPES_OK;
+}
+
+SPES_API int spes_moe_router_aux(const spes_moe_shape* shape, void* ctx, float lb_coef, float z_coef, float grad_scale,
+                                 float* losses, void* stream) {
+  SPES_TRY(shape_supported(shape));
+  if (!ctx || !losses) return SPES_EINVAL;
+  if (!aligned16(ctx)) return SPES_EALIGN;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const Layout L = make_layout(shape);
+  return launch_router_aux(at<float>(ctx, L.pub.logits), at<float>(ctx, L.pub.lse), at<int>(ctx, L.pub.offset), shape->T,
+                           shape->n_experts, shape->top_k, lb_coef, z_coef, grad_scale, at<float>(ctx, L.aux_part), losses,
+                           at<float>(ctx, L.aux), s);
 }
 
 SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const void* x, const void* w_router,
@@ -256,7 +271,7 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
   prof_mark(1, "gemm_dgrad_down_dswiglu", s);
   SPES_TRY(launch_gating_bwd(at<float>(ctx, L.pub.logits), at<float>(ctx, L.pub.lse), idx, gate, at<float>(ctx, L.dgate_part),
                              n_part, R, inv, at<float>(ctx, L.pub.dgate), T, M, k, shape->renorm_topk,
-                             at<float>(ctx, L.pub.dlogits), router_mfma ? at<bf16_t>(ctx, L.dlogits_bf) : nullptr, s));
+                             at<float>(ctx, L.aux), at<float>(ctx, L.pub.dlogits), router_mfma ? at<bf16_t>(ctx, L.dlogits_bf) : nullptr, s));
   prof_mark(1, "gating_bwd", s);
   // dxp = da W_g + db W_u
   {

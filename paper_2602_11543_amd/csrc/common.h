@@ -9,6 +9,8 @@ namespace spes {
 
 constexpr int kWave = 64;
 constexpr int kMaxExperts = 64;   // one router score per lane of a wavefront
+constexpr int kAuxExtra = 2;      // floats after the per-expert factors of the auxiliary-loss gradient record
+constexpr int kAuxBlocks = 256;   // upper bound on the partial sums of the auxiliary router losses
 
 typedef uint16_t bf16_t;          // raw bf16 bit pattern
 

@@ -11,10 +11,13 @@ int launch_topk_gate(float* logits, int n_part, const float* bias, int T, int M,
                      int* idx_copy, float* gate_copy, float* lse, hipStream_t s);
 int launch_routing_tables(const int* idx, const float* gate, int R, int M, int k, int* block_counts, int* expert_count,
                           int* offset, int* perm, int* inv, int* row_token, float* row_gate, int bm0, int* tab0, int bm1,
-                          int* tab1, int max_tiles, hipStream_t s);
+                          int* tab1, int max_tiles, float* aux, hipStream_t s);
 int launch_gating_bwd(const float* logits, const float* lse, const int* idx, const float* gate, const float* dgate_part,
-                      int n_part, long part_stride, const int* inv, float* dgate, int T, int M, int k, int renorm, float* dlogits,
-                      bf16_t* dlogits_bf, hipStream_t s);
+                      int n_part, long part_stride, const int* inv, float* dgate, int T, int M, int k, int renorm, const float* aux,
+                      float* dlogits, bf16_t* dlogits_bf, hipStream_t s);
+// losses[0] = load-balancing loss, losses[1] = router z-loss; aux = the gradient factors read by launch_gating_bwd
+int launch_router_aux(const float* logits, const float* lse, const int* offset, int T, int M, int k, float lb_coef, float z_coef,
+                      float grad_scale, float* part, float* losses, float* aux, hipStream_t s);
 
 // movement.hip (dtype = spes_dtype of the storage type)
 int launch_permute(int dtype, const void* x, const int* inv, int k, void* xp, int T, int d, hipStream_t s);

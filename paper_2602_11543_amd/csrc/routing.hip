@@ -83,8 +83,11 @@ __device__ __forceinline__ int wave_exclusive_scan(int v, int lane) {
 // first positions, and writes counts, offsets and the row-tile tables.
 __global__ __launch_bounds__(64) void scan_kernel(int* __restrict__ block_counts, int nblk, int M, int* __restrict__ expert_count,
                                                   int* __restrict__ offset, int bm0, int* __restrict__ tab0, int bm1,
-                                                  int* __restrict__ tab1, int max_tiles) {
+                                                  int* __restrict__ tab1, int max_tiles, float* __restrict__ aux) {
   const int e = threadIdx.x;
+  // a new forward pass withdraws the auxiliary-loss gradient terms left for the previous backward pass
+  aux[e] = 0.f;
+  if (e < kAuxExtra) aux[kMaxExperts + e] = 0.f;
   int total = 0;
 #pragma unroll 8
   for (int b = 0; b < nblk; ++b) total += block_counts[b * kMaxExperts + e];
@@ -177,8 +180,8 @@ __global__ __launch_bounds__(256) void gating_bwd_kernel(const float* __restrict
                                                          const int* __restrict__ topk_idx, const float* __restrict__ topk_gate,
                                                          const float* __restrict__ dgate_part, int n_part, long part_stride,
                                                          const int* __restrict__ inv, float* __restrict__ dgate, int T, int M,
-                                                         int k, int renorm, float* __restrict__ dlogits,
-                                                         bf16_t* __restrict__ dlogits_bf) {
+                                                         int k, int renorm, const float* __restrict__ aux,
+                                                         float* __restrict__ dlogits, bf16_t* __restrict__ dlogits_bf) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= T) return;
@@ -192,6 +195,8 @@ __global__ __launch_bounds__(256) void gating_bwd_kernel(const float* __restrict
     dgate[(long)t * k + lane] = dg;
   }
   float out = 0.f;
+  const float lse_t = lse[t];
+  const float p = (lane < M) ? expf(logits[(long)t * M + lane] - lse_t) : 0.f;
   if (renorm) {
     const float dot = wave_sum(g * dg);
     const float mine = g * (dg - dot);
@@ -202,7 +207,6 @@ __global__ __launch_bounds__(256) void gating_bwd_kernel(const float* __restrict
       if (lane == ej) out = vj;
     }
   } else {
-    const float p = (lane < M) ? expf(logits[(long)t * M + lane] - lse[t]) : 0.f;
     float dp = 0.f;
     for (int j = 0; j < k; ++j) {
       const int ej = __shfl(sel, j, kWave);
@@ -212,10 +216,58 @@ __global__ __launch_bounds__(256) void gating_bwd_kernel(const float* __restrict
     const float dot = wave_sum(dp * p);
     out = p * (dp - dot);
   }
+  // auxiliary router losses: aux[e] = dL/dp_e of the load-balancing term (the same for every token),
+  // aux[kMaxExperts] = the z-loss factor 2 z / T; both are zero unless armed after the forward pass
+  {
+    const float c = (lane < M) ? aux[lane] : 0.f;
+    const float cp = wave_sum(c * p);
+    out += p * (c - cp) + aux[kMaxExperts] * lse_t * p;
+  }
   if (lane < M) {
     dlogits[(long)t * M + lane] = out;
     if (dlogits_bf != nullptr) dlogits_bf[(long)t * M + lane] = f32_to_bf16(out);
   }
+}
+
+// Partial sums for the auxiliary router losses: per block, sum_t p_te for every expert and sum_t lse_t^2.
+__global__ __launch_bounds__(256) void aux_partial_kernel(const float* __restrict__ logits, const float* __restrict__ lse, int T,
+                                                          int M, float* __restrict__ part) {
+  __shared__ float acc[4][kMaxExperts + 1];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  float ps = 0.f, zs = 0.f;
+  for (int t = blockIdx.x * 4 + w; t < T; t += gridDim.x * 4) {
+    const float l = lse[t];
+    if (lane < M) ps += expf(logits[(long)t * M + lane] - l);
+    zs = fmaf(l, l, zs);
+  }
+  acc[w][lane] = ps;
+  if (lane == 0) acc[w][kMaxExperts] = zs;
+  __syncthreads();
+  if (w == 0) {
+    part[blockIdx.x * (kMaxExperts + 1) + lane] = (acc[0][lane] + acc[1][lane]) + (acc[2][lane] + acc[3][lane]);
+    if (lane == 0)
+      part[blockIdx.x * (kMaxExperts + 1) + kMaxExperts] =
+          (acc[0][kMaxExperts] + acc[1][kMaxExperts]) + (acc[2][kMaxExperts] + acc[3][kMaxExperts]);
+  }
+}
+
+// L_lb = M sum_e f_e P_e and L_z = mean_t lse_t^2 from the block partials (fixed summation order), and the
+// gradient factors the gating backward kernel applies.
+__global__ __launch_bounds__(64) void aux_final_kernel(const float* __restrict__ part, int nblk, const int* __restrict__ offset,
+                                                       int T, int M, int k, float lb_coef, float z_coef, float grad_scale,
+                                                       float* __restrict__ losses, float* __restrict__ aux) {
+  const int e = threadIdx.x;
+  float ps = 0.f, zs = 0.f;
+  for (int b = 0; b < nblk; ++b) {
+    ps += part[b * (kMaxExperts + 1) + e];
+    zs += part[b * (kMaxExperts + 1) + kMaxExperts];
+  }
+  const float f = (e < M) ? (float)(offset[e + 1] - offset[e]) / ((float)T * (float)k) : 0.f;
+  const float P = (e < M) ? ps / (float)T : 0.f;
+  const float lb = (float)M * wave_sum(f * P);
+  if (e == 0) { losses[0] = lb; losses[1] = zs / (float)T; }
+  aux[e] = grad_scale * lb_coef * (float)M * f / (float)T;
+  if (e == 0) aux[kMaxExperts] = grad_scale * z_coef * 2.f / (float)T;
 }
 
 }  // namespace
@@ -231,20 +283,28 @@ int launch_topk_gate(float* logits, int n_part, const float* bias, int T, int M,
 
 int launch_routing_tables(const int* idx, const float* gate, int R, int M, int k, int* block_counts, int* expert_count,
                           int* offset, int* perm, int* inv, int* row_token, float* row_gate, int bm0, int* tab0, int bm1,
-                          int* tab1, int max_tiles, hipStream_t s) {
+                          int* tab1, int max_tiles, float* aux, hipStream_t s) {
   const int nblk = routing_blocks(R);
   hipLaunchKernelGGL(count_kernel, dim3(nblk), dim3(256), 0, s, idx, R, block_counts);
   hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(64), 0, s, block_counts, nblk, M, expert_count, offset, bm0, tab0, bm1, tab1,
-                     max_tiles);
+                     max_tiles, aux);
   hipLaunchKernelGGL(scatter_kernel, dim3(nblk), dim3(256), 0, s, idx, gate, R, k, block_counts, perm, inv, row_token, row_gate);
   return hipGetLastError() == hipSuccess ? SPES_OK : SPES_EHIP;
 }
 
 int launch_gating_bwd(const float* logits, const float* lse, const int* idx, const float* gate, const float* dgate_part,
-                      int n_part, long part_stride, const int* inv, float* dgate, int T, int M, int k, int renorm, float* dlogits,
-                      bf16_t* dlogits_bf, hipStream_t s) {
+                      int n_part, long part_stride, const int* inv, float* dgate, int T, int M, int k, int renorm, const float* aux,
+                      float* dlogits, bf16_t* dlogits_bf, hipStream_t s) {
   hipLaunchKernelGGL(gating_bwd_kernel, dim3(cdiv(T, 4)), dim3(256), 0, s, logits, lse, idx, gate, dgate_part, n_part, part_stride,
-                     inv, dgate, T, M, k, renorm, dlogits, dlogits_bf);
+                     inv, dgate, T, M, k, renorm, aux, dlogits, dlogits_bf);
+  return hipGetLastError() == hipSuccess ? SPES_OK : SPES_EHIP;
+}
+
+int launch_router_aux(const float* logits, const float* lse, const int* offset, int T, int M, int k, float lb_coef, float z_coef,
+                      float grad_scale, float* part, float* losses, float* aux, hipStream_t s) {
+  const int nblk = cdiv(T, 4 * 16) < kAuxBlocks ? cdiv(T, 4 * 16) : kAuxBlocks;
+  hipLaunchKernelGGL(aux_partial_kernel, dim3(nblk), dim3(256), 0, s, logits, lse, T, M, part);
+  hipLaunchKernelGGL(aux_final_kernel, dim3(1), dim3(64), 0, s, part, nblk, offset, T, M, k, lb_coef, z_coef, grad_scale, losses, aux);
   return hipGetLastError() == hipSuccess ? SPES_OK : SPES_EHIP;
 }
 

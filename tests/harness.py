@@ -65,6 +65,12 @@ class DeviceLayer:
         S.spes_moe_bwd(self.shape, self.dy, self.x, self.w_router, self.w_gate, self.w_up, self.w_down, self.ctx, self.mask,
                        self.dx, self.d_w_router, self.d_w_gate, self.d_w_up, self.d_w_down, accumulate)
 
+    def aux(self, lb_coef, z_coef, grad_scale=1.0):
+        """Router auxiliary losses of the last forward; arms the next bwd.  Returns (L_lb, L_z)."""
+        losses = torch.zeros(2, dtype=torch.float32, device=self.dev)
+        S.spes_moe_router_aux(self.shape, self.ctx, lb_coef, z_coef, grad_scale, losses)
+        return tuple(float(v) for v in losses.cpu().numpy())
+
     def view(self, name):
         return S.ctx_view(self.shape, self.ctx, name)
 
