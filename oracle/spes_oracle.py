@@ -20,6 +20,8 @@ order of appearance):
   arithmetic, all right-hand sides pre-merge)                   -- Sec. 3.3, Eq. 5-6; App. A merge step
 * router auxiliary losses: load-balancing loss and router
   z-loss, with the coefficients of the implementation details   -- Sec. 3.3 "Training Losses"; App. B
+* AdamW on the assigned experts and the shared parameters only
+  (the "3 x |Phi_i|" of the memory model)                       -- Sec. 3.3 "Efficiency Analysis"; App. B, Table A1
 
 Every function takes numpy arrays of already-rounded inputs and up-converts them
 to float64; nothing is blocked, fused or reordered beyond "for each expert, the
@@ -346,3 +348,32 @@ def warmup_merge(phi, nbr, alpha):
             acc += phi[int(kk)] - phi[j]
         out[j] = phi[j] + (alpha / K) * acc
     return out
+
+
+# ----------------------------------------------------------------------------
+# optimizer step on the trainable subset: Sec. 3.3 "Efficiency Analysis" (gradients and the two AdamW
+# moments exist only for the assigned experts and the shared parameters); hyper-parameters App. B, Table A1
+# ----------------------------------------------------------------------------
+
+def adamw_step(w, m, v, g, lr, beta1, beta2, eps, weight_decay, step, grad_scale=1.0):
+    """One AdamW update (decoupled weight decay) of the arrays w, m, v with gradient grad_scale * g at step
+    number `step` (1-based).  Returns new (w, m, v); nothing is rounded."""
+    w, m, v, g = _f64(w), _f64(m), _f64(v), _f64(g) * grad_scale
+    m = beta1 * m + (1.0 - beta1) * g
+    v = beta2 * v + (1.0 - beta2) * g * g
+    m_hat = m / (1.0 - beta1 ** step)
+    v_hat = v / (1.0 - beta2 ** step)
+    w = w - lr * (m_hat / (np.sqrt(v_hat) + eps) + weight_decay * w)
+    return w, m, v
+
+
+def masked_adamw(param, trainable, master, m, v, grad, **hyper):
+    """The update applied to a full expert store: expert e = trainable[s] owns slot s of the compact arrays
+    master/m/v/grad [n_trainable, ...]; every other expert is left untouched.  Returns (param, master, m, v) with
+    param[e] = new master[s] (the caller rounds it to the storage type)."""
+    param = _f64(param).copy()
+    master, m, v = _f64(master).copy(), _f64(m).copy(), _f64(v).copy()
+    for s_, e in enumerate(trainable):
+        master[s_], m[s_], v[s_] = adamw_step(master[s_], m[s_], v[s_], grad[s_], **hyper)
+        param[e] = master[s_]
+    return param, master, m, v
