@@ -120,14 +120,86 @@ def bench_merge(args) -> int:
     return 0
 
 
+def bench_train_step(args) -> int:
+    """One node's whole update of the layer: forward, auxiliary router losses, backward, AdamW on the trainable experts
+    and the router (the headline workload plus the two neighbouring stages, timed separately)."""
+    import numpy as np
+    import torch
+
+    import paper_2602_11543_amd as S
+    from spes_workloads import CONFIGS, layer_inputs
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from harness import DeviceLayer
+
+    cfg = CONFIGS[args.config]
+    dev = torch.device("cuda:0")
+    L = DeviceLayer(layer_inputs(cfg), dev)
+    n, M, d, f = len(L.trainable), cfg.M, cfg.d, cfg.f
+    dt = S.SPES_F32 if cfg.dtype == "f32" else S.SPES_BF16
+    hyper = dict(lr=5e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1)
+    state = []
+    for w, g, elems in ((L.w_gate, L.d_w_gate, f * d), (L.w_up, L.d_w_up, f * d), (L.w_down, L.d_w_down, d * f)):
+        master = w[L.trainable].float().reshape(n, elems).contiguous()
+        state.append((w, L.mask, master, torch.zeros_like(master), torch.zeros_like(master), g, M, elems))
+    rmaster = L.w_router.float().reshape(1, M * d).contiguous()
+    state.append((L.w_router, np.ones(1, dtype=np.uint8), rmaster, torch.zeros_like(rmaster), torch.zeros_like(rmaster),
+                  L.d_w_router, 1, M * d))
+    losses = torch.zeros(2, dtype=torch.float32, device=dev)
+    step_no = [0]
+
+    def optim():
+        step_no[0] += 1
+        for w, mask, master, m, v, g, ne, elems in state:
+            S.spes_masked_adamw(ne, elems, dt, w, mask, master, m, v, g, step=step_no[0], **hyper)
+
+    def aux():
+        S.spes_moe_router_aux(L.shape, L.ctx, 0.01, 0.001, 1.0, losses)
+
+    def timed(parts, steps, warmup):
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(parts) + 1)] for _ in range(steps)]
+        for _ in range(warmup):
+            for fn in parts:
+                fn()
+        torch.cuda.synchronize()
+        for i in range(steps):
+            ev[i][0].record()
+            for j, fn in enumerate(parts):
+                fn()
+                ev[i][j + 1].record()
+        torch.cuda.synchronize()
+        return [sum(ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(steps)) / steps for j in range(len(parts))]
+
+    t_fwd, t_aux, t_bwd, t_opt = timed([L.fwd, aux, L.bwd, optim], args.steps, args.warmup)
+    total = t_fwd + t_aux + t_bwd + t_opt
+    es = 4 if cfg.dtype == "f32" else 2
+    opt_elems = 3 * n * d * f + M * d
+    opt_bytes = opt_elems * (28 + es)          # grad, m, v, w in; m, v, w out; the storage-type copy out
+    aux_bytes = cfg.T * M * 4 + cfg.T * 4      # scores and log-sum-exp read once
+    out = {"metric": "MoE layer training step (fwd + aux losses + bwd + AdamW on the trainable subset) tokens/sec on 1 MI355X",
+           "value": round(cfg.T / total * 1e3, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(total, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+           "config": {"workload": f"{cfg.name}: T={cfg.T} d_model={cfg.d} experts={M} d_ff={f} top_k={cfg.k} trainable={n}/{M}"},
+           "stages": {"fwd": {"ms": round(t_fwd, 4)}, "bwd": {"ms": round(t_bwd, 4)},
+                      "router_aux": {"ms": round(t_aux, 4), "bound": "hbm", "achieved": round(aux_bytes / t_aux / 1e6, 1),
+                                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(aux_bytes / t_aux / 1e6 / PEAK_HBM_GBS, 4)},
+                      "masked_adamw": {"ms": round(t_opt, 4), "bound": "hbm", "bytes": opt_bytes,
+                                       "achieved": round(opt_bytes / t_opt / 1e6, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                       "frac": round(opt_bytes / t_opt / 1e6 / PEAK_HBM_GBS, 4)}},
+           "losses": {"load_balancing": float(losses[0]), "router_z": float(losses[1])}}
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="cfg2", help="workload name from spes_workloads.CONFIGS")
-    ap.add_argument("--workload", default="layer", choices=["layer", "merge"],
-                    help="layer: fwd+bwd of the MoE layer (the headline metric); merge: expert synchronisation sweep")
+    ap.add_argument("--workload", default="layer", choices=["layer", "merge", "step"],
+                    help="layer: fwd+bwd of the MoE layer (the headline metric); merge: expert synchronisation sweep; "
+                         "step: fwd + auxiliary losses + bwd + AdamW on the trainable subset")
     ap.add_argument("--cpu-sample", type=int, default=16384, help="tokens of the workload timed through the fp64 oracle (0: skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -136,6 +208,8 @@ def main() -> int:
 
     if args.workload == "merge":
         return bench_merge(args)
+    if args.workload == "step":
+        return bench_train_step(args)
 
     import numpy as np
     import torch

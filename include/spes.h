@@ -149,6 +149,31 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
 SPES_API int spes_moe_router_aux(const spes_moe_shape* shape, void* ctx, float lb_coef,
                                  float z_coef, float grad_scale, float* losses, void* stream);
 
+/* AdamW step on the trainable subset of one parameter matrix of the expert store.  A node keeps
+ * gradients and the two optimizer moments only for its assigned experts and for the shared
+ * parameters (Sec. 3.3 "Efficiency Analysis", the 3 x |Phi_i| term of the memory model), so all
+ * optimizer state is compact: one slot per expert whose mask byte is non-zero, in ascending expert
+ * id, exactly like the gradient buffers of spes_moe_bwd.  Per element, with g = grad_scale * grad,
+ *      m <- beta1 m + (1-beta1) g          v <- beta2 v + (1-beta2) g^2
+ *      w <- w - lr ( (m / (1-beta1^step)) / (sqrt(v / (1-beta2^step)) + eps) + weight_decay w )
+ * in fp32 (Table A1: beta 0.9 / 0.95, eps 1e-8, weight decay 0.1), then the expert's row of the
+ * full store is overwritten with w rounded to the storage type.  Frozen experts are not touched.
+ * A shared matrix such as the router is the case n_experts = 1, mask = {1}.
+ *
+ *  n_experts >= 1; elems = elements of the matrix per expert, a multiple of 8
+ *  param        DEVICE [n_experts, elems] storage dtype, in/out
+ *  trainable_mask HOST [n_experts] bytes
+ *  master       DEVICE [n_trainable, elems] f32 in/out: the fp32 weights; NULL is allowed for
+ *               dtype f32 only, then param itself is the weight
+ *  m, v         DEVICE [n_trainable, elems] f32 in/out
+ *  grad         DEVICE [n_trainable, elems] f32
+ *  step         >= 1, the number of this update (bias correction)
+ */
+SPES_API int spes_masked_adamw(int32_t n_experts, int64_t elems, int32_t dtype, void* param,
+                               const uint8_t* trainable_mask, float* master, float* m, float* v,
+                               const float* grad, float lr, float beta1, float beta2, float eps,
+                               float weight_decay, int32_t step, float grad_scale, void* stream);
+
 /* Synchronisation of node-local expert copies (Sec. 3.3 Eq. 4; App. A sync rules),
  * for one parameter matrix of every expert.  Expert j becomes the weighted mean
  * of the copies held by the nodes that trained it,

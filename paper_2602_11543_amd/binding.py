@@ -51,6 +51,8 @@ def _load() -> ctypes.CDLL:
     lib.spes_moe_bwd.argtypes = [shp] + [vp] * 13 + [i32, vp]
     lib.spes_moe_router_aux.restype = i32
     lib.spes_moe_router_aux.argtypes = [shp, vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, vp, vp]
+    lib.spes_masked_adamw.restype = i32
+    lib.spes_masked_adamw.argtypes = [i32, i64, i32, vp, vp, vp, vp, vp, vp] + [ctypes.c_float] * 5 + [i32, ctypes.c_float, vp]
     lib.spes_expert_merge.restype = i32
     lib.spes_expert_merge.argtypes = [i32, i64, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.spes_warmup_scratch_bytes.restype = sz
@@ -134,6 +136,16 @@ def spes_moe_bwd(shape, dy, x, w_router, w_gate, w_up, w_down, ctx, trainable_ma
 def spes_moe_router_aux(shape, ctx, lb_coef, z_coef, grad_scale, losses, stream=None) -> None:
     _check(_lib.spes_moe_router_aux(ctypes.byref(shape), _dev(ctx), float(lb_coef), float(z_coef), float(grad_scale),
                                     _dev(losses), _stream(stream)), "spes_moe_router_aux")
+
+
+def spes_masked_adamw(n_experts, elems, dtype, param, trainable_mask, master, m, v, grad, lr, beta1, beta2, eps, weight_decay,
+                      step, grad_scale=1.0, stream=None) -> None:
+    mask = np.ascontiguousarray(trainable_mask, dtype=np.uint8)
+    if mask.shape != (n_experts,):
+        raise SpesError("trainable_mask must have one byte per expert")
+    _check(_lib.spes_masked_adamw(n_experts, elems, dtype, _dev(param), mask.ctypes.data_as(ctypes.c_void_p), _dev(master),
+                                  _dev(m), _dev(v), _dev(grad), float(lr), float(beta1), float(beta2), float(eps),
+                                  float(weight_decay), int(step), float(grad_scale), _stream(stream)), "spes_masked_adamw")
 
 
 def spes_expert_merge(n_experts, elems, dtype, node_store: Sequence[Optional[torch.Tensor]], slot, node_weight, dst,

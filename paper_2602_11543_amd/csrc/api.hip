@@ -343,6 +343,22 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
   return SPES_OK;
 }
 
+SPES_API int spes_masked_adamw(int32_t n_experts, int64_t elems, int32_t dtype, void* param, const uint8_t* trainable_mask,
+                               float* master, float* m, float* v, const float* grad, float lr, float beta1, float beta2,
+                               float eps, float weight_decay, int32_t step, float grad_scale, void* stream) {
+  if (n_experts < 1 || elems < 1 || step < 1 || (dtype != SPES_F32 && dtype != SPES_BF16) || !param || !trainable_mask)
+    return SPES_EINVAL;
+  if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f)) return SPES_EINVAL;
+  if (elems % 8) return SPES_ESHAPE;
+  bool any = false;
+  for (int e = 0; e < n_experts; ++e) any = any || trainable_mask[e];
+  if (!any) return SPES_OK;
+  if (!m || !v || !grad || (!master && dtype != SPES_F32)) return SPES_EINVAL;
+  if (!aligned16(param) || !aligned16(m) || !aligned16(v) || !aligned16(grad) || (master && !aligned16(master))) return SPES_EALIGN;
+  return launch_masked_adamw(dtype, n_experts, elems, param, trainable_mask, master, m, v, grad, lr, beta1, beta2, eps,
+                             weight_decay, step, grad_scale, static_cast<hipStream_t>(stream));
+}
+
 SPES_API int spes_expert_merge(int32_t n_experts, int64_t elems, int32_t dtype, int32_t n_nodes,
                                const void* const* node_store, const int32_t* slot, const float* node_weight, void* dst,
                                int32_t* trainer_count, void* stream) {

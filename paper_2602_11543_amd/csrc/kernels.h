@@ -35,4 +35,9 @@ int launch_sync_merge(int dtype, int n_experts, long elems, int n_nodes, const v
 int launch_sim_topk(float* partial, int n_partial, int M, int K, float* sim, int* nbr, hipStream_t s);
 int launch_warmup_mix(int dtype, int M, long elems, int K, float alpha, const void* src, void* dst, const int* nbr, hipStream_t s);
 
+// optim.hip: AdamW on the experts whose mask byte is set; compact fp32 state, one slot per such expert in ascending id
+int launch_masked_adamw(int dtype, int n_experts, long elems, void* param, const unsigned char* mask, float* master, float* m,
+                        float* v, const float* grad, float lr, float beta1, float beta2, float eps, float wd, int step,
+                        float grad_scale, hipStream_t s);
+
 }  // namespace spes

@@ -235,7 +235,23 @@ __global__ __launch_bounds__(256) void aux_partial_kernel(const float* __restric
   __shared__ float acc[4][kMaxExperts + 1];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   float ps = 0.f, zs = 0.f;
-  for (int t = blockIdx.x * 4 + w; t < T; t += gridDim.x * 4) {
+  // four tokens per step keep four independent loads in flight; the summation order is fixed by the grid alone
+  const int step = gridDim.x * 4;
+  int t = blockIdx.x * 4 + w;
+  for (; t + 3 * step < T; t += 4 * step) {
+    float l[4], x[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      l[u] = lse[t + u * step];
+      x[u] = (lane < M) ? logits[(long)(t + u * step) * M + lane] : -INFINITY;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      ps += expf(x[u] - l[u]);
+      zs = fmaf(l[u], l[u], zs);
+    }
+  }
+  for (; t < T; t += step) {
     const float l = lse[t];
     if (lane < M) ps += expf(logits[(long)t * M + lane] - l);
     zs = fmaf(l, l, zs);
@@ -253,15 +269,22 @@ __global__ __launch_bounds__(256) void aux_partial_kernel(const float* __restric
 
 // L_lb = M sum_e f_e P_e and L_z = mean_t lse_t^2 from the block partials (fixed summation order), and the
 // gradient factors the gating backward kernel applies.
-__global__ __launch_bounds__(64) void aux_final_kernel(const float* __restrict__ part, int nblk, const int* __restrict__ offset,
-                                                       int T, int M, int k, float lb_coef, float z_coef, float grad_scale,
-                                                       float* __restrict__ losses, float* __restrict__ aux) {
-  const int e = threadIdx.x;
+__global__ __launch_bounds__(256) void aux_final_kernel(const float* __restrict__ part, int nblk, const int* __restrict__ offset,
+                                                        int T, int M, int k, float lb_coef, float z_coef, float grad_scale,
+                                                        float* __restrict__ losses, float* __restrict__ aux) {
+  __shared__ float acc[4][kMaxExperts + 1];
+  const int e = threadIdx.x & 63, w = threadIdx.x >> 6;
   float ps = 0.f, zs = 0.f;
-  for (int b = 0; b < nblk; ++b) {
+  for (int b = w; b < nblk; b += 4) {          // wavefront w adds blocks w, w+4, ...; the four sums are then added in order
     ps += part[b * (kMaxExperts + 1) + e];
     zs += part[b * (kMaxExperts + 1) + kMaxExperts];
   }
+  acc[w][e] = ps;
+  if (e == 0) acc[w][kMaxExperts] = zs;
+  __syncthreads();
+  if (w != 0) return;
+  ps = (acc[0][e] + acc[1][e]) + (acc[2][e] + acc[3][e]);
+  zs = (acc[0][kMaxExperts] + acc[1][kMaxExperts]) + (acc[2][kMaxExperts] + acc[3][kMaxExperts]);
   const float f = (e < M) ? (float)(offset[e + 1] - offset[e]) / ((float)T * (float)k) : 0.f;
   const float P = (e < M) ? ps / (float)T : 0.f;
   const float lb = (float)M * wave_sum(f * P);
@@ -304,7 +327,7 @@ int launch_router_aux(const float* logits, const float* lse, const int* offset, 
                       float grad_scale, float* part, float* losses, float* aux, hipStream_t s) {
   const int nblk = cdiv(T, 4 * 16) < kAuxBlocks ? cdiv(T, 4 * 16) : kAuxBlocks;
   hipLaunchKernelGGL(aux_partial_kernel, dim3(nblk), dim3(256), 0, s, logits, lse, T, M, part);
-  hipLaunchKernelGGL(aux_final_kernel, dim3(1), dim3(64), 0, s, part, nblk, offset, T, M, k, lb_coef, z_coef, grad_scale, losses, aux);
+  hipLaunchKernelGGL(aux_final_kernel, dim3(1), dim3(256), 0, s, part, nblk, offset, T, M, k, lb_coef, z_coef, grad_scale, losses, aux);
   return hipGetLastError() == hipSuccess ? SPES_OK : SPES_EHIP;
 }
 

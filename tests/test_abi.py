@@ -69,6 +69,16 @@ def test_argument_checks_run_before_any_launch():
                                         ctypes.c_void_p, ctypes.c_void_p]
     assert lib.spes_moe_router_aux(ctypes.byref(ok_shape), None, 0.01, 0.001, 1.0, p[0], None) == -1      # no ctx
     assert lib.spes_moe_router_aux(ctypes.byref(ok_shape), p[0], 0.01, 0.001, 1.0, None, None) == -1      # no output
+    lib.spes_masked_adamw.restype = ctypes.c_int32
+    lib.spes_masked_adamw.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int32] + [ctypes.c_void_p] * 6 + \
+        [ctypes.c_float] * 5 + [ctypes.c_int32, ctypes.c_float, ctypes.c_void_p]
+    m2 = ctypes.cast((ctypes.c_uint8 * 2)(1, 0), ctypes.c_void_p)
+    adam = lambda elems, dtype, master, step, b1=0.9: lib.spes_masked_adamw(
+        2, elems, dtype, p[0], m2, master, p[2], p[3], p[4], 5e-4, b1, 0.95, 1e-8, 0.1, step, 1.0, None)
+    assert adam(64, 1, None, 1) == -1             # a bf16 store needs fp32 weights
+    assert adam(64, 1, p[1], 0) == -1             # steps count from 1
+    assert adam(64, 1, p[1], 1, b1=1.0) == -1     # beta must be below 1
+    assert adam(60, 1, p[1], 1) == -2             # elems not a multiple of 8
     slot = (ctypes.c_int32 * 4)(0, -1, -1, 0)
     stores = (ctypes.c_void_p * 2)(0x20000, 0x30000)
     args = lambda elems, dtype: (2, ctypes.c_int64(elems), dtype, 2, ctypes.cast(stores, ctypes.c_void_p),
