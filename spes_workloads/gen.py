@@ -92,6 +92,12 @@ CONFIGS: Dict[str, MoEConfig] = {
     "cfg3_small": MoEConfig("cfg3_small", 1531, 512, 64, 352, 8, "bf16", 0, 8, "random", "gumbel", 1.0, 0.02, False, _BASE_SEED + 13),
     "cfg4_small": MoEConfig("cfg4_small", 777, 448, 32, 608, 2, "bf16", 1, 8, "random", "none", 0.0, 1e-3, True, _BASE_SEED + 14),
     "cfg1_bf16": MoEConfig("cfg1_bf16", 512, 256, 8, 512, 2, "bf16", 1, 4, "first", "none", 0.0, 0.02, False, _BASE_SEED + 15),
+    # the layer shapes of the paper's own models (Sec. 4, model-configuration table) at one micro-batch of
+    # 2 x 2048 tokens; trainable experts = experts / nodes of the corresponding experiment; the 9B model is upcycled
+    "paper_1b": MoEConfig("paper_1b", 4096, 768, 16, 2048, 2, "bf16", 0, 4, "random", "none", 0.0, 0.02, False, _BASE_SEED + 21),
+    "paper_2b": MoEConfig("paper_2b", 4096, 1536, 16, 1280, 2, "bf16", 0, 1, "random", "none", 0.0, 0.02, False, _BASE_SEED + 22),
+    "paper_7b": MoEConfig("paper_7b", 4096, 2048, 32, 2048, 4, "bf16", 0, 8, "random", "none", 0.0, 0.02, False, _BASE_SEED + 23),
+    "paper_9b": MoEConfig("paper_9b", 4096, 2048, 8, 6144, 2, "bf16", 1, 2, "random", "none", 0.0, 1e-3, True, _BASE_SEED + 24),
     "cfg2_f32": MoEConfig("cfg2_f32", 300, 128, 16, 96, 4, "f32", 0, 5, "random", "normal", 0.5, 0.02, False, _BASE_SEED + 16),
 }
 
@@ -191,9 +197,10 @@ def trainable_mask(cfg: MoEConfig) -> np.ndarray:
     return m
 
 
-def tokens_with_margin(cfg: MoEConfig, w_router: np.ndarray, bias: Optional[np.ndarray]):
-    """x [T,d] ~ N(0,1) in storage precision; tokens whose router margin is < MARGIN are redrawn."""
-    x = to_storage(_normal(cfg.seed, "x", (cfg.T, cfg.d), 1.0), cfg.dtype)
+def tokens_with_margin(cfg: MoEConfig, w_router: np.ndarray, bias: Optional[np.ndarray], micro: int = 0):
+    """x [T,d] ~ N(0,1) in storage precision; tokens whose router margin is < MARGIN are redrawn.
+    `micro` selects an independent stream (micro-batch number) under the same seed."""
+    x = to_storage(_normal(cfg.seed, "x", (cfg.T, cfg.d), 1.0, sub=micro), cfg.dtype)
     redraws = 0
     bad = np.nonzero(min_topk_gap(x, w_router, bias, cfg.k) < MARGIN)[0]
     attempt = 1
@@ -202,7 +209,7 @@ def tokens_with_margin(cfg: MoEConfig, w_router: np.ndarray, bias: Optional[np.n
             raise RuntimeError(f"{cfg.name}: {bad.size} tokens still below margin after {attempt} attempts")
         redraws += bad.size
         # one fresh stream per attempt; row i of the attempt replaces token bad[i]
-        fresh = to_storage(_normal(cfg.seed, "x", (bad.size, cfg.d), 1.0, attempt=attempt), cfg.dtype)
+        fresh = to_storage(_normal(cfg.seed, "x", (bad.size, cfg.d), 1.0, sub=micro, attempt=attempt), cfg.dtype)
         x[bad] = fresh
         still = min_topk_gap(fresh, w_router, bias, cfg.k) < MARGIN
         bad = bad[still]
@@ -210,17 +217,18 @@ def tokens_with_margin(cfg: MoEConfig, w_router: np.ndarray, bias: Optional[np.n
     return x, redraws
 
 
-def layer_inputs(cfg: MoEConfig, weights: bool = True) -> dict:
+def layer_inputs(cfg: MoEConfig, weights: bool = True, micro: int = 0) -> dict:
     """All inputs of one fwd+bwd pass of the layer for `cfg`.
 
     Keys: x [T,d], w_router [M,d], router_bias [M] or None, w_gate/w_up [M,f,d],
     w_down [M,d,f], dy [T,d], trainable_mask uint8 [M], redraw_fraction.
+    `micro` > 0 gives another micro-batch (x, dy) for the same weights.
     """
     w_router = to_storage(_normal(cfg.seed, "w_router", (cfg.M, cfg.d), cfg.router_sigma), cfg.dtype)
     bias = router_bias(cfg)
-    x, redraws = tokens_with_margin(cfg, w_router, bias)
+    x, redraws = tokens_with_margin(cfg, w_router, bias, micro)
     out = dict(cfg=cfg, x=x, w_router=w_router, router_bias=bias,
-               dy=to_storage(_normal(cfg.seed, "dy", (cfg.T, cfg.d), 1.0), cfg.dtype),
+               dy=to_storage(_normal(cfg.seed, "dy", (cfg.T, cfg.d), 1.0, sub=micro), cfg.dtype),
                trainable_mask=trainable_mask(cfg), redraw_fraction=redraws / cfg.T)
     if weights:
         for w in ("w_gate", "w_up", "w_down"):
