@@ -26,6 +26,45 @@ PEAK_FP32_TFLOPS = 157.3      # fp32 vector/matrix peak (fp32 storage mode)
 PEAK_HBM_GBS = 8000.0         # HBM3E
 
 
+# kernel behind each single-launch stage, as named in the rocprofv3 summaries under profiles/
+STAGE_KERNEL = {
+    "gemm_gate_up_swiglu": "gemm_mfma_kernel<0, 1, true, true, false",
+    "gemm_down": "gemm_mfma_kernel<0, 0, true, true, false",
+    "gemm_dgrad_down_dswiglu": "gemm_mfma_kernel<0, 2, true, false, false",
+    "gemm_dgrad_gate_up": "gemm_mfma_kernel<0, 0, true, false, false",
+    "wgrad_down": "gemm_mfma_kernel<1, 0, false, false, true",
+    "permute": "permute_kernel",
+    "combine": "combine_kernel",
+}
+
+
+def profiled_traffic(cfg_name: str, stage: str):
+    """HBM-side bytes per launch of the stage's kernel from the committed counter summary of this workload
+    (FETCH_SIZE and WRITE_SIZE in KiB, each scaled by what the same counter reads for a plain copy of known size),
+    or None when there is no summary for the workload or the stage is not a single kernel of its own."""
+    path = os.path.join(ROOT, "profiles", f"moe_layer_{cfg_name}.txt")
+    kernel = STAGE_KERNEL.get(stage)
+    if kernel is None or not os.path.exists(path):
+        return None
+    fetch = write = None
+    sf = sw = None
+    in_table = False
+    for line in open(path):
+        if line.startswith("# HBM traffic per dispatch"):
+            in_table = True
+        elif in_table and line.startswith(kernel):
+            cols = line.split()
+            fetch, write = float(cols[-2]), float(cols[-1])
+        elif line.startswith("# scale factors:"):
+            nums = [float(t.lstrip("x").rstrip(",")) for t in line.split() if t.startswith("x")]
+            if len(nums) == 2:
+                sf, sw = nums
+    if None in (fetch, write, sf, sw):
+        return None
+    return {"bytes": int((fetch * sf + write * sw) * 1024), "fetch_bytes": int(fetch * sf * 1024), "write_bytes": int(write * sw * 1024),
+            "source": f"profiles/moe_layer_{cfg_name}.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, calibrated on a 1 GiB copy)"}
+
+
 def stage_model(cfg, rho_rows):
     """Algorithmic work of every stage: (bound, amount) with amount in FLOP (mfma/alu) or bytes (hbm)."""
     T, d, M, f, k = cfg.T, cfg.d, cfg.M, cfg.f, cfg.k
@@ -305,6 +344,10 @@ def main() -> int:
                                "what": "plain 1 GiB device-to-device copy (read + write bytes) on this GPU"},
         "stages": stages,
     }
+    tr = profiled_traffic(cfg.name, dominant)
+    if tr is not None:
+        out["roofline"]["traffic"] = tr["bytes"]           # HBM-side bytes per launch (offline counters, see traffic_detail)
+        out["roofline"]["traffic_detail"] = tr
 
     if args.cpu_sample > 0:
         from oracle import spes_oracle as O
