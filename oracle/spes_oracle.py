@@ -22,6 +22,9 @@ order of appearance):
   z-loss, with the coefficients of the implementation details   -- Sec. 3.3 "Training Losses"; App. B
 * AdamW on the assigned experts and the shared parameters only
   (the "3 x |Phi_i|" of the memory model)                       -- Sec. 3.3 "Efficiency Analysis"; App. B, Table A1
+* only the trained experts travel at a synchronisation           -- Sec. 3.3 (sparse synchronisation), Eq. 4
+* upcycling: replicate one dense FFN, add Gaussian noise to a
+  share of the parameters                                       -- Sec. 4 "upcycling settings"
 
 Every function takes numpy arrays of already-rounded inputs and up-converts them
 to float64; nothing is blocked, fused or reordered beyond "for each expert, the
@@ -377,3 +380,79 @@ def masked_adamw(param, trainable, master, m, v, grad, **hyper):
         master[s_], m[s_], v[s_] = adamw_step(master[s_], m[s_], v[s_], grad[s_], **hyper)
         param[e] = master[s_]
     return param, master, m, v
+
+
+# ----------------------------------------------------------------------------
+# what a node uploads at a synchronisation: the rows of its trained experts, contiguous (Sec. 3.3, Eq. 4)
+# ----------------------------------------------------------------------------
+
+def pack_experts(store, trainable):
+    """[n_trainable, ...] copy of the rows `trainable` (ascending expert ids) of the full store."""
+    return np.asarray(store)[list(trainable)].copy()
+
+
+def unpack_experts(store, trainable, packed):
+    """The full store with the rows `trainable` replaced by `packed`; every other row unchanged."""
+    out = np.asarray(store).copy()
+    for s_, e in enumerate(trainable):
+        out[e] = packed[s_]
+    return out
+
+
+# ----------------------------------------------------------------------------
+# upcycling initialiser (Sec. 4 "upcycling settings": the dense FFN is replicated and Gaussian noise of standard
+# deviation 0.02 is added to 50 % of the parameters).  The random draws are defined by a counter-based generator so
+# that the device can reproduce them: Philox-4x64-10 (Salmon et al., SC'11) keyed by the seed, one call per group
+# of four consecutive elements of the [M, elems] output.
+# ----------------------------------------------------------------------------
+
+_PHILOX_M0, _PHILOX_M1 = 0xD2E7470EE14C6C93, 0xCA5A826395121157
+_PHILOX_W0, _PHILOX_W1 = 0x9E3779B97F4A7C15, 0xBB67AE8584CAA73B
+_U64 = (1 << 64) - 1
+
+
+def philox4x64(counter, key, rounds=10):
+    """The Philox-4x64 bijection on one 256-bit counter (four Python ints) under a 128-bit key (two ints)."""
+    c0, c1, c2, c3 = [int(c) & _U64 for c in counter]
+    k0, k1 = [int(k) & _U64 for k in key]
+    for _ in range(rounds):
+        p0, p1 = _PHILOX_M0 * c0, _PHILOX_M1 * c2
+        c0, c1, c2, c3 = ((p1 >> 64) ^ c1 ^ k0) & _U64, p1 & _U64, ((p0 >> 64) ^ c3 ^ k1) & _U64, p0 & _U64
+        k0, k1 = (k0 + _PHILOX_W0) & _U64, (k1 + _PHILOX_W1) & _U64
+    return c0, c1, c2, c3
+
+
+def upcycle_draws(group_index, seed, stream_id):
+    """Random draws for the four elements of group `group_index` (= flat element index // 4 of the [M, elems]
+    output): returns (select_byte[4], normal[4]).
+
+    One generator call with counter (group_index, stream_id, 0, 0) and key (seed, 0) yields four 64-bit words
+    w_0..w_3.  Element j is selected iff the low byte of w_j is below fraction * 256.  The standard normals come from
+    Box-Muller: elements 2q and 2q+1 are r cos(t) and r sin(t) with r = sqrt(-2 ln u1), t = 2 pi u2,
+    u1 = (top 24 bits of w_{2q} + 0.5) / 2^24 and u2 = (top 24 bits of w_{2q+1} + 0.5) / 2^24.
+    """
+    w = philox4x64((group_index, stream_id, 0, 0), (seed, 0))
+    sel = [x & 0xFF for x in w]
+    z = []
+    for q in range(2):
+        u1 = ((w[2 * q] >> 40) + 0.5) / 16777216.0
+        u2 = ((w[2 * q + 1] >> 40) + 0.5) / 16777216.0
+        r = np.sqrt(-2.0 * np.log(u1))
+        z += [r * np.cos(2.0 * np.pi * u2), r * np.sin(2.0 * np.pi * u2)]
+    return sel, z
+
+
+def upcycle_init(dense, n_experts, fraction, sigma, seed, stream_id=0):
+    """out[e] = dense + select * sigma * z with the draws above; dense is one flattened matrix [elems] (elems a
+    multiple of 4).  Nothing is rounded here."""
+    dense = _f64(dense).ravel()
+    elems = dense.size
+    thr = int(np.floor(fraction * 256.0))
+    out = np.empty((n_experts, elems))
+    for e in range(n_experts):
+        for g in range(elems // 4):
+            sel, z = upcycle_draws((e * elems) // 4 + g, seed, stream_id)
+            for j in range(4):
+                i = 4 * g + j
+                out[e, i] = dense[i] + (sigma * z[j] if sel[j] < thr else 0.0)
+    return out
