@@ -230,15 +230,58 @@ def bench_train_step(args) -> int:
     return 0
 
 
+def bench_init(args) -> int:
+    """Upcycling initialiser and upload packing on the upcycled workload's shape (32 experts of 4864 x 3584, bf16)."""
+    import numpy as np
+    import torch
+
+    import paper_2602_11543_amd as S
+
+    dev = torch.device("cuda:0")
+    M, elems, n_tr = 32, 4864 * 3584, 8
+    dense = (torch.randn(elems, device=dev) * 0.02).to(torch.bfloat16)
+    out = torch.empty(M, elems, dtype=torch.bfloat16, device=dev)
+    mask = np.zeros(M, dtype=np.uint8); mask[np.random.default_rng(0).choice(M, n_tr, replace=False)] = 1
+    packed = torch.empty(n_tr, elems, dtype=torch.bfloat16, device=dev)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(args.steps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / args.steps
+
+    ms_up = timed(lambda: S.spes_upcycle_init(M, elems, S.SPES_BF16, dense, 0.5, 0.02, 7, 1, out))
+    ms_pk = timed(lambda: S.spes_expert_pack(M, elems, S.SPES_BF16, out, mask, packed, 0))
+    by_up = 2 * elems * (M + 1)                 # every expert written once; the dense matrix read (cache-served after the first)
+    by_pk = 2 * 2 * elems * n_tr
+    res = lambda ms, by: {"ms": round(ms, 4), "bytes": by, "bound": "hbm", "achieved": round(by / ms / 1e6, 1), "peak": PEAK_HBM_GBS,
+                          "unit": "GB/s", "frac": round(by / ms / 1e6 / PEAK_HBM_GBS, 4)}
+    out_j = {"metric": "upcycling initialiser GB/s on 1 MI355X", "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+             "warmup": args.warmup, "dtype": "bf16", "data": "synthetic",
+             "config": {"workload": f"{M} experts x {elems} elements from one dense matrix, noise on 50 %; pack of {n_tr} experts"},
+             "upcycle_init": res(ms_up, by_up), "expert_pack": res(ms_pk, by_pk)}
+    # the initialiser is bound by the generator's 64-bit integer multiplies, not by memory: no roofline claim
+    out_j["upcycle_init"].update(bound="alu", peak=None, frac=None)
+    out_j["value"] = out_j["upcycle_init"]["achieved"]
+    print(json.dumps(out_j))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="cfg2", help="workload name from spes_workloads.CONFIGS")
-    ap.add_argument("--workload", default="layer", choices=["layer", "merge", "step"],
+    ap.add_argument("--workload", default="layer", choices=["layer", "merge", "step", "init"],
                     help="layer: fwd+bwd of the MoE layer (the headline metric); merge: expert synchronisation sweep; "
-                         "step: fwd + auxiliary losses + bwd + AdamW on the trainable subset")
+                         "step: fwd + auxiliary losses + bwd + AdamW on the trainable subset; init: upcycling initialiser and upload packing")
     ap.add_argument("--cpu-sample", type=int, default=16384, help="tokens of the workload timed through the fp64 oracle (0: skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -249,6 +292,8 @@ def main() -> int:
         return bench_merge(args)
     if args.workload == "step":
         return bench_train_step(args)
+    if args.workload == "init":
+        return bench_init(args)
 
     import numpy as np
     import torch

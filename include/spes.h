@@ -174,6 +174,34 @@ SPES_API int spes_masked_adamw(int32_t n_experts, int64_t elems, int32_t dtype, 
                                const float* grad, float lr, float beta1, float beta2, float eps,
                                float weight_decay, int32_t step, float grad_scale, void* stream);
 
+/* Upcycling initialiser (Sec. 4, upcycling settings: the dense FFN is replicated into the experts
+ * and Gaussian noise of standard deviation 0.02 is added to 50 % of the parameters), for one
+ * parameter matrix:  out[e][i] = dense[i] + select(e,i) * sigma * z(e,i),  rounded to the storage type.
+ * The draws are a pure function of (seed, stream_id, e*elems + i): Philox-4x64-10 with key (seed, 0)
+ * and counter (g, stream_id, 0, 0) yields words w_0..w_3 for the group g of four consecutive flat
+ * indices; element j is selected iff (w_j & 255) < floor(fraction * 256); z of elements 2q, 2q+1 is
+ * r cos(2 pi u2), r sin(2 pi u2) with r = sqrt(-2 ln u1), u1 = ((w_2q >> 40) + 0.5) / 2^24,
+ * u2 = ((w_2q+1 >> 40) + 0.5) / 2^24.  Use a different stream_id per parameter matrix.
+ *
+ *  n_experts >= 1; elems a multiple of 8; 0 <= fraction <= 1; sigma >= 0
+ *  dense  DEVICE [elems]            out  DEVICE [n_experts, elems]
+ */
+SPES_API int spes_upcycle_init(int32_t n_experts, int64_t elems, int32_t dtype, const void* dense,
+                               float fraction, float sigma, uint64_t seed, uint64_t stream_id,
+                               void* out, void* stream);
+
+/* Gather (to_store = 0) or scatter (to_store = 1) of the rows of the experts whose mask byte is
+ * non-zero between the full store and a contiguous buffer with one row per such expert in ascending
+ * expert id: what a node uploads at a synchronisation is only what it trained (Sec. 3.3, Eq. 4),
+ * and the buffer has the layout spes_expert_merge reads as a node store.
+ *
+ *  store   DEVICE [n_experts, elems]   packed  DEVICE [n_trainable, elems]   elems a multiple of 8
+ *  trainable_mask HOST [n_experts] bytes
+ */
+SPES_API int spes_expert_pack(int32_t n_experts, int64_t elems, int32_t dtype, void* store,
+                              const uint8_t* trainable_mask, void* packed, int32_t to_store,
+                              void* stream);
+
 /* Synchronisation of node-local expert copies (Sec. 3.3 Eq. 4; App. A sync rules),
  * for one parameter matrix of every expert.  Expert j becomes the weighted mean
  * of the copies held by the nodes that trained it,

@@ -53,6 +53,10 @@ def _load() -> ctypes.CDLL:
     lib.spes_moe_router_aux.argtypes = [shp, vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, vp, vp]
     lib.spes_masked_adamw.restype = i32
     lib.spes_masked_adamw.argtypes = [i32, i64, i32, vp, vp, vp, vp, vp, vp] + [ctypes.c_float] * 5 + [i32, ctypes.c_float, vp]
+    lib.spes_upcycle_init.restype = i32
+    lib.spes_upcycle_init.argtypes = [i32, i64, i32, vp, ctypes.c_float, ctypes.c_float, ctypes.c_uint64, ctypes.c_uint64, vp, vp]
+    lib.spes_expert_pack.restype = i32
+    lib.spes_expert_pack.argtypes = [i32, i64, i32, vp, vp, vp, i32, vp]
     lib.spes_expert_merge.restype = i32
     lib.spes_expert_merge.argtypes = [i32, i64, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.spes_warmup_scratch_bytes.restype = sz
@@ -146,6 +150,19 @@ def spes_masked_adamw(n_experts, elems, dtype, param, trainable_mask, master, m,
     _check(_lib.spes_masked_adamw(n_experts, elems, dtype, _dev(param), mask.ctypes.data_as(ctypes.c_void_p), _dev(master),
                                   _dev(m), _dev(v), _dev(grad), float(lr), float(beta1), float(beta2), float(eps),
                                   float(weight_decay), int(step), float(grad_scale), _stream(stream)), "spes_masked_adamw")
+
+
+def spes_upcycle_init(n_experts, elems, dtype, dense, fraction, sigma, seed, stream_id, out, stream=None) -> None:
+    _check(_lib.spes_upcycle_init(n_experts, elems, dtype, _dev(dense), float(fraction), float(sigma), int(seed), int(stream_id),
+                                  _dev(out), _stream(stream)), "spes_upcycle_init")
+
+
+def spes_expert_pack(n_experts, elems, dtype, store, trainable_mask, packed, to_store=0, stream=None) -> None:
+    mask = np.ascontiguousarray(trainable_mask, dtype=np.uint8)
+    if mask.shape != (n_experts,):
+        raise SpesError("trainable_mask must have one byte per expert")
+    _check(_lib.spes_expert_pack(n_experts, elems, dtype, _dev(store), mask.ctypes.data_as(ctypes.c_void_p), _dev(packed),
+                                 int(to_store), _stream(stream)), "spes_expert_pack")
 
 
 def spes_expert_merge(n_experts, elems, dtype, node_store: Sequence[Optional[torch.Tensor]], slot, node_weight, dst,

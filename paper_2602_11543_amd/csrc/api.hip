@@ -1,5 +1,6 @@
 // C ABI of the library: argument checks, context layout and the launch
 // sequences of the forward, backward, synchronisation and warm-up merge.
+#include <cmath>
 #include <cstring>
 
 #include "kernels.h"
@@ -357,6 +358,28 @@ SPES_API int spes_masked_adamw(int32_t n_experts, int64_t elems, int32_t dtype, 
   if (!aligned16(param) || !aligned16(m) || !aligned16(v) || !aligned16(grad) || (master && !aligned16(master))) return SPES_EALIGN;
   return launch_masked_adamw(dtype, n_experts, elems, param, trainable_mask, master, m, v, grad, lr, beta1, beta2, eps,
                              weight_decay, step, grad_scale, static_cast<hipStream_t>(stream));
+}
+
+SPES_API int spes_upcycle_init(int32_t n_experts, int64_t elems, int32_t dtype, const void* dense, float fraction, float sigma,
+                               uint64_t seed, uint64_t stream_id, void* out, void* stream) {
+  if (n_experts < 1 || elems < 1 || (dtype != SPES_F32 && dtype != SPES_BF16) || !dense || !out) return SPES_EINVAL;
+  if (!(fraction >= 0.f && fraction <= 1.f) || !(sigma >= 0.f)) return SPES_EINVAL;
+  if (elems % 8) return SPES_ESHAPE;
+  if (!aligned16(dense) || !aligned16(out)) return SPES_EALIGN;
+  const unsigned thr = (unsigned)floor((double)fraction * 256.0);
+  return launch_upcycle_init(dtype, n_experts, elems, dense, thr, sigma, seed, stream_id, out, static_cast<hipStream_t>(stream));
+}
+
+SPES_API int spes_expert_pack(int32_t n_experts, int64_t elems, int32_t dtype, void* store, const uint8_t* trainable_mask,
+                              void* packed, int32_t to_store, void* stream) {
+  if (n_experts < 1 || elems < 1 || (dtype != SPES_F32 && dtype != SPES_BF16) || !store || !trainable_mask) return SPES_EINVAL;
+  if (elems % 8) return SPES_ESHAPE;
+  bool any = false;
+  for (int e = 0; e < n_experts; ++e) any = any || trainable_mask[e];
+  if (!any) return SPES_OK;
+  if (!packed) return SPES_EINVAL;
+  if (!aligned16(store) || !aligned16(packed)) return SPES_EALIGN;
+  return launch_expert_pack(dtype, n_experts, elems, store, trainable_mask, packed, to_store != 0, static_cast<hipStream_t>(stream));
 }
 
 SPES_API int spes_expert_merge(int32_t n_experts, int64_t elems, int32_t dtype, int32_t n_nodes,

@@ -40,4 +40,11 @@ int launch_masked_adamw(int dtype, int n_experts, long elems, void* param, const
                         float* v, const float* grad, float lr, float beta1, float beta2, float eps, float wd, int step,
                         float grad_scale, hipStream_t s);
 
+// upcycle.hip: out[e] = dense + noise on the selected share of the elements (thr = selected 256ths); gather / scatter
+// of the rows of the experts whose mask byte is set between the full store and a contiguous buffer
+int launch_upcycle_init(int dtype, int n_experts, long elems, const void* dense, unsigned thr, float sigma,
+                        unsigned long long seed, unsigned long long stream_id, void* out, hipStream_t s);
+int launch_expert_pack(int dtype, int n_experts, long elems, void* store, const unsigned char* mask, void* packed, int to_store,
+                       hipStream_t s);
+
 }  // namespace spes

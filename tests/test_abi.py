@@ -79,6 +79,17 @@ def test_argument_checks_run_before_any_launch():
     assert adam(64, 1, p[1], 0) == -1             # steps count from 1
     assert adam(64, 1, p[1], 1, b1=1.0) == -1     # beta must be below 1
     assert adam(60, 1, p[1], 1) == -2             # elems not a multiple of 8
+    lib.spes_upcycle_init.restype = ctypes.c_int32
+    lib.spes_upcycle_init.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_float,
+                                      ctypes.c_float, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]
+    assert lib.spes_upcycle_init(4, 64, 1, p[0], 1.5, 0.02, 1, 0, p[1], None) == -1      # fraction above 1
+    assert lib.spes_upcycle_init(4, 60, 1, p[0], 0.5, 0.02, 1, 0, p[1], None) == -2      # elems not a multiple of 8
+    assert lib.spes_upcycle_init(4, 64, 1, _fake(0x10008), 0.5, 0.02, 1, 0, p[1], None) == -3
+    lib.spes_expert_pack.restype = ctypes.c_int32
+    lib.spes_expert_pack.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                     ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p]
+    assert lib.spes_expert_pack(2, 64, 1, p[0], m2, None, 0, None) == -1                 # a trainable expert but no buffer
+    assert lib.spes_expert_pack(2, 60, 1, p[0], m2, p[1], 0, None) == -2
     slot = (ctypes.c_int32 * 4)(0, -1, -1, 0)
     stores = (ctypes.c_void_p * 2)(0x20000, 0x30000)
     args = lambda elems, dtype: (2, ctypes.c_int64(elems), dtype, 2, ctypes.cast(stores, ctypes.c_void_p),
