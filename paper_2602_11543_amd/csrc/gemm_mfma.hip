@@ -292,29 +292,35 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   bf16x8 fa[2][TM], fb[2][TN];
   const int tr_k = lhalf * 8 + (lane & 15) / 4;                  // k-row (within a k-step) this lane points the transposing read at
   const int tr_r = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;      // row (within a 32-row MFMA tile) likewise
-  auto read_frags = [&](int stage, int ks, int set) {
+  auto read_frag_a = [&](int stage, int ks, int set, int i) {
     const uint4* ta = smem + stage * C::STAGE_VEC;
-    const uint4* tb = ta + C::A_VEC;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      if (A_KC) {
-        fa[set][i] = __builtin_bit_cast(bf16x8, ta[(wm * (BM / 2) + i * 32 + l32) * C::PITCH + ks * 2 + lhalf]);
-      } else {
-        const bf16_t* p = reinterpret_cast<const bf16_t*>(ta + (ks * 16 + tr_k) * C::KPA) + wm * (BM / 2) + i * 32 + tr_r;
-        const uint2 lo = lds_read_tr(p), hi = lds_read_tr(p + 4 * C::KPA * 8);
-        fa[set][i] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
-      }
+    if (A_KC) {
+      fa[set][i] = __builtin_bit_cast(bf16x8, ta[(wm * (BM / 2) + i * 32 + l32) * C::PITCH + ks * 2 + lhalf]);
+    } else {
+      const bf16_t* p = reinterpret_cast<const bf16_t*>(ta + (ks * 16 + tr_k) * C::KPA) + wm * (BM / 2) + i * 32 + tr_r;
+      const uint2 lo = lds_read_tr(p), hi = lds_read_tr(p + 4 * C::KPA * 8);
+      fa[set][i] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
     }
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      if (B_KC) {
-        fb[set][j] = __builtin_bit_cast(bf16x8, tb[(wn * (BN / 2) + j * 32 + l32) * C::PITCH + ks * 2 + lhalf]);
-      } else {
-        const bf16_t* p = reinterpret_cast<const bf16_t*>(tb + (ks * 16 + tr_k) * C::KPB) + wn * (BN / 2) + j * 32 + tr_r;
-        const uint2 lo = lds_read_tr(p), hi = lds_read_tr(p + 4 * C::KPB * 8);
-        fb[set][j] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
-      }
+  };
+  auto read_frag_b = [&](int stage, int ks, int set, int j) {
+    const uint4* tb = smem + stage * C::STAGE_VEC + C::A_VEC;
+    if (B_KC) {
+      fb[set][j] = __builtin_bit_cast(bf16x8, tb[(wn * (BN / 2) + j * 32 + l32) * C::PITCH + ks * 2 + lhalf]);
+    } else {
+      const bf16_t* p = reinterpret_cast<const bf16_t*>(tb + (ks * 16 + tr_k) * C::KPB) + wn * (BN / 2) + j * 32 + tr_r;
+      const uint2 lo = lds_read_tr(p), hi = lds_read_tr(p + 4 * C::KPB * 8);
+      fb[set][j] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
     }
+  };
+  // fragment w of a k-step in the order the MFMAs first need them: B0, A0 .. A(TM-1), B1 .. B(TN-1)
+  auto read_frag = [&](int stage, int ks, int set, int w) {
+    if (w == 0) read_frag_b(stage, ks, set, 0);
+    else if (w <= TM) read_frag_a(stage, ks, set, w - 1);
+    else read_frag_b(stage, ks, set, w - TM);
+  };
+  auto read_frags = [&](int stage, int ks, int set) {
+#pragma unroll
+    for (int w = 0; w < TM + TN; ++w) read_frag(stage, ks, set, w);
   };
 
   if (nsteps > 0) {
@@ -341,21 +347,25 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
 #pragma unroll
       for (int ks = 0; ks < C::KSTEPS; ++ks) {
         const int set = ks & 1;
-        if (ks + 1 < C::KSTEPS) {
-          read_frags(cur, ks + 1, set ^ 1);
-        } else {
-          read_frags(cur ^ 1, 0, set ^ 1);     // next K-tile, published by the barrier below
-        }
+        // next k-step's stage: after the last k-step comes the next K-tile, published by the barrier below
+        const int nstage = (ks + 1 < C::KSTEPS) ? cur : cur ^ 1, nks = (ks + 1 < C::KSTEPS) ? ks + 1 : 0;
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int q = 0; q < MF; ++q) {
           const int j = q / TM, i = q % TM;
           acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[j][i], 0, 0, 0);
+          // everything else is dealt out over the gaps between MFMAs in portions that fit under one MFMA:
+          // one fragment read of the next k-step every FR-th gap, and per staging register its LDS write in
+          // one gap and its reload in the next
+          constexpr int FR = MF / (TM + TN);
+          if (q % FR == 0) read_frag(nstage, nks, set ^ 1, q / FR);
           if (ks < C::KSTEPS - 1) {
             const int slot = ks * MF + q;
 #pragma unroll
-            for (int p = 0; p < NP; ++p)
-              if (p * SLOTS / NP == slot) piece(p, cur ^ 1, true, true);
+            for (int p = 0; p < NP; ++p) {
+              if (p * SLOTS / NP == slot) piece(p, cur ^ 1, true, false);
+              if (p * SLOTS / NP + 1 == slot) piece(p, cur ^ 1, false, true);
+            }
           }
           __builtin_amdgcn_sched_barrier(0);
         }
