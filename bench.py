@@ -283,6 +283,7 @@ def main() -> int:
                     help="layer: fwd+bwd of the MoE layer (the headline metric); merge: expert synchronisation sweep; "
                          "step: fwd + auxiliary losses + bwd + AdamW on the trainable subset; init: upcycling initialiser and upload packing")
     ap.add_argument("--cpu-sample", type=int, default=16384, help="tokens of the workload timed through the fp64 oracle (0: skip)")
+    ap.add_argument("--graph", action="store_true", help="layer workload: replay the step from a captured HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -329,12 +330,25 @@ def main() -> int:
     copy_gbs = 3 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
     del src, dst
 
+    run = step
+    if args.graph:
+        # the step recorded once into a HIP graph and replayed: removes the per-kernel launch cost, which is what the
+        # small launch-bound workload spends most of its time on
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            step()
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.synchronize()
+        run = graph.replay
     for _ in range(args.warmup):
-        step()
+        run()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     tokens_per_s = cfg.T / (ms_per_step * 1e-3)
@@ -380,7 +394,7 @@ def main() -> int:
                                f"renorm={cfg.renorm} trainable={cfg.n_trainable}/{cfg.M} ({cfg.dtype}, fp32 accumulate)",
                    "trainable_row_fraction": round(rows_trainable / (cfg.T * cfg.k), 4),
                    "max_over_mean_expert_load": round(float(count.max() / count.mean()), 2),
-                   "input_generation_s": round(gen_s, 1)},
+                   "input_generation_s": round(gen_s, 1), "hip_graph": bool(args.graph)},
         "roofline": {"kernel": dominant, "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
                      "unit": dom["unit"], "frac": dom["frac"], "traffic": None},
         "grouped_gemm_util": {"flop": gemm_flop, "ms": round(gemm_ms, 4), "achieved_tflops": round(gemm_flop / (gemm_ms * 1e-3) / 1e12, 2),
