@@ -417,6 +417,31 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   __syncthreads();                                   // the staging tiles are dead from here on
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
+    if (EPI == kEpiStore && !g.c_f32) {
+      // bf16 output: round first, so that half as many bytes make the trip through LDS; rows of ECOLS bf16 with a
+      // pitch of ECOLS*2+8 bytes (the 32 rows one write instruction touches fall into different banks)
+      constexpr int BPITCH = ECOLS * 2 + 8;
+      char* eb = reinterpret_cast<char*>(ep);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq)
+          *reinterpret_cast<uint2*>(eb + l32 * BPITCH + (j * 32 + gq * 8 + lhalf * 4) * 2) =
+              make_uint2(pack2(acc[j][i][gq * 4], acc[j][i][gq * 4 + 1]), pack2(acc[j][i][gq * 4 + 2], acc[j][i][gq * 4 + 3]));
+      constexpr int CPR = ECOLS / 8, RPI = 64 / CPR;   // lanes per row (eight columns each), rows per access
+      const int c8 = lane % CPR;
+      const long n = n0 + wn * (BN / 2) + c8 * 8;
+#pragma unroll
+      for (int st = 0; st < 32 / RPI; ++st) {
+        const int row = st * RPI + lane / CPR;
+        const uint2 lo = *reinterpret_cast<const uint2*>(eb + row * BPITCH + c8 * 16);
+        const uint2 hi = *reinterpret_cast<const uint2*>(eb + row * BPITCH + c8 * 16 + 8);
+        const long m = m_base + i * 32 + row;
+        if (m < m_end && n < g.Ndim)
+          *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(g.C[0]) + c_group + m * g.c_ms + n) = make_uint4(lo.x, lo.y, hi.x, hi.y);
+      }
+      continue;
+    }
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -433,15 +458,10 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
         const float4 v = *reinterpret_cast<const float4*>(ep + row * EPITCH + c4 * 4);
         const long m = m_base + i * 32 + row;
         if (m < m_end && n < g.Ndim) {
-          const long ci = c_group + m * g.c_ms + n;
-          if (g.c_f32) {
-            float4* c = reinterpret_cast<float4*>(reinterpret_cast<float*>(g.C[0]) + ci);
-            float4 o = v;
-            if (g.accumulate) { const float4 old = *c; o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w; }
-            *c = o;
-          } else {
-            *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.C[0]) + ci) = make_uint2(pack2(v.x, v.y), pack2(v.z, v.w));
-          }
+          float4* c = reinterpret_cast<float4*>(reinterpret_cast<float*>(g.C[0]) + c_group + m * g.c_ms + n);
+          float4 o = v;
+          if (g.accumulate) { const float4 old = *c; o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w; }
+          *c = o;
         }
       }
     } else if (EPI == kEpiSwiglu) {
