@@ -385,11 +385,11 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   constexpr int ECOLS = TN * 32, EPITCH = ECOLS + 4; // floats per LDS row (pitch keeps the writes conflict-free)
   float* ep = reinterpret_cast<float*>(smem) + wave * (32 * EPITCH);
   const long m_base = m0 + wm * (BM / 2);
-  // dSwiGLU epilogue: lanes lie along the columns (DS_CPR lanes per row, four columns each); the saved fp32
-  // projections come in batches of half a 32-row slab
-  constexpr int DS_CPR = ECOLS / 4, DS_RPI = 64 / DS_CPR, DS_NB = 2, DS_HALF = 32 / DS_RPI / DS_NB;
-  const int ds_c4 = lane % DS_CPR;
-  const long ds_n = n0 + wn * (BN / 2) + ds_c4 * 4;
+  // dSwiGLU epilogue: lanes lie along the columns (DS_CPR lanes per row, eight columns each, so that the bf16
+  // results leave in 16-byte stores); the saved fp32 projections come in batches of half a 32-row slab
+  constexpr int DS_CPR = ECOLS / 8, DS_RPI = 64 / DS_CPR, DS_NB = 2, DS_HALF = 32 / DS_RPI / DS_NB;
+  const int ds_c8 = lane % DS_CPR;
+  const long ds_n = n0 + wn * (BN / 2) + ds_c8 * 8;
   // addresses are a per-tile base (uniform) plus a 32-bit offset: one register per address instead of two
   const long ds_tile = m0 * g.c_ms;
   const int ds_rows = (int)(m_end - m0);                        // valid rows of the tile
@@ -401,15 +401,17 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   bf16_t* ds_c0 = reinterpret_cast<bf16_t*>(g.C[0]) + ds_tile;
   bf16_t* ds_c1 = reinterpret_cast<bf16_t*>(g.C[1]) + ds_tile;
   bf16_t* ds_c2 = reinterpret_cast<bf16_t*>(g.C[2]) + ds_tile;
-  float4 av[EPI == kEpiDSwiglu ? DS_HALF : 1], bv[EPI == kEpiDSwiglu ? DS_HALF : 1];
+  float4 av[EPI == kEpiDSwiglu ? DS_HALF : 1][2], bv[EPI == kEpiDSwiglu ? DS_HALF : 1][2];
   auto load_ab = [&](int i, int hf) {
     if (EPI == kEpiDSwiglu) {
 #pragma unroll
       for (int q = 0; q < DS_HALF; ++q) {
         const int rt = ds_r0 + i * 32 + (hf * DS_HALF + q) * DS_RPI;     // row within the tile
         const unsigned ci = (unsigned)(rt < ds_rows ? rt : ds_rows - 1) * (unsigned)g.c_ms + ds_ncl;
-        av[q] = *reinterpret_cast<const float4*>(ds_a + ci);
-        bv[q] = *reinterpret_cast<const float4*>(ds_b + ci);
+        av[q][0] = *reinterpret_cast<const float4*>(ds_a + ci);
+        av[q][1] = *reinterpret_cast<const float4*>(ds_a + ci + 4);
+        bv[q][0] = *reinterpret_cast<const float4*>(ds_b + ci);
+        bv[q][1] = *reinterpret_cast<const float4*>(ds_b + ci + 4);
       }
     }
   };
@@ -489,19 +491,21 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
     } else {
 #pragma unroll
       for (int hf = 0; hf < DS_NB; ++hf) {
-        uint2 oa[DS_HALF], ob[DS_HALF], oh[DS_HALF];
+        uint4 oa[DS_HALF], ob[DS_HALF], oh[DS_HALF];
         float dots[DS_HALF];
 #pragma unroll
         for (int q = 0; q < DS_HALF; ++q) {
           const int row = (hf * DS_HALF + q) * DS_RPI + lane / DS_CPR;
-          const float4 uv = *reinterpret_cast<const float4*>(ep + row * EPITCH + ds_c4 * 4);
+          const float4 u0 = *reinterpret_cast<const float4*>(ep + row * EPITCH + ds_c8 * 8);
+          const float4 u1 = *reinterpret_cast<const float4*>(ep + row * EPITCH + ds_c8 * 8 + 4);
           const int rt = ds_r0 + i * 32 + (hf * DS_HALF + q) * DS_RPI;
           const float rs = g.row_scale[m0 + (rt < ds_rows ? rt : ds_rows - 1)];
-          const float u[4] = {uv.x, uv.y, uv.z, uv.w}, a[4] = {av[q].x, av[q].y, av[q].z, av[q].w},
-                      b[4] = {bv[q].x, bv[q].y, bv[q].z, bv[q].w};
-          float da[4], db[4], hg[4], dot = 0.f;
+          const float u[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w},
+                      a[8] = {av[q][0].x, av[q][0].y, av[q][0].z, av[q][0].w, av[q][1].x, av[q][1].y, av[q][1].z, av[q][1].w},
+                      b[8] = {bv[q][0].x, bv[q][0].y, bv[q][0].z, bv[q][0].w, bv[q][1].x, bv[q][1].y, bv[q][1].z, bv[q][1].w};
+          float da[8], db[8], hg[8], dot = 0.f;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
+          for (int e = 0; e < 8; ++e) {
             const float sg = sigmoidf_(a[e]);
             const float as = a[e] * sg;          // SiLU(a)
             const float h = as * b[e];
@@ -511,9 +515,9 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
             db[e] = dh * as;
             hg[e] = rs * h;
           }
-          oa[q] = make_uint2(pack2(da[0], da[1]), pack2(da[2], da[3]));
-          ob[q] = make_uint2(pack2(db[0], db[1]), pack2(db[2], db[3]));
-          oh[q] = make_uint2(pack2(hg[0], hg[1]), pack2(hg[2], hg[3]));
+          oa[q] = make_uint4(pack2(da[0], da[1]), pack2(da[2], da[3]), pack2(da[4], da[5]), pack2(da[6], da[7]));
+          ob[q] = make_uint4(pack2(db[0], db[1]), pack2(db[2], db[3]), pack2(db[4], db[5]), pack2(db[6], db[7]));
+          oh[q] = make_uint4(pack2(hg[0], hg[1]), pack2(hg[2], hg[3]), pack2(hg[4], hg[5]), pack2(hg[6], hg[7]));
           if (!(rt < ds_rows && ds_nin)) dot = 0.f;
           // gate-gradient partial of this row over the wavefront's columns: the CPR lanes of a row sit side by side
 #pragma unroll
@@ -532,11 +536,11 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
           const int rt = ds_r0 + i * 32 + (hf * DS_HALF + q) * DS_RPI;
           if (rt < ds_rows && ds_nin) {
             const unsigned ci = (unsigned)rt * (unsigned)g.c_ms + ds_ncl;
-            *reinterpret_cast<uint2*>(ds_c0 + ci) = oa[q];
-            *reinterpret_cast<uint2*>(ds_c1 + ci) = ob[q];
-            *reinterpret_cast<uint2*>(ds_c2 + ci) = oh[q];
+            *reinterpret_cast<uint4*>(ds_c0 + ci) = oa[q];
+            *reinterpret_cast<uint4*>(ds_c1 + ci) = ob[q];
+            *reinterpret_cast<uint4*>(ds_c2 + ci) = oh[q];
           }
-          if (ds_c4 == 0 && rt < ds_rows) g.rowdot[(long)(nt * 2 + wn) * g.rowdot_stride + m0 + rt] = dots[q];
+          if (ds_c8 == 0 && rt < ds_rows) g.rowdot[(long)(nt * 2 + wn) * g.rowdot_stride + m0 + rt] = dots[q];
         }
       }
     }
