@@ -447,9 +447,13 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int gq = 0; gq < 4; ++gq)
-        *reinterpret_cast<float4*>(ep + l32 * EPITCH + j * 32 + gq * 8 + lhalf * 4) =
+      for (int gq = 0; gq < 4; ++gq) {
+        // the dSwiGLU epilogue reads two adjacent 4-column groups per lane: even groups are kept in the first half
+        // of the LDS row and odd groups in the second, so that each of its reads is contiguous across the lanes
+        const int col = (EPI == kEpiDSwiglu) ? lhalf * (ECOLS / 2) + (j * 4 + gq) * 4 : j * 32 + gq * 8 + lhalf * 4;
+        *reinterpret_cast<float4*>(ep + l32 * EPITCH + col) =
             make_float4(acc[j][i][gq * 4], acc[j][i][gq * 4 + 1], acc[j][i][gq * 4 + 2], acc[j][i][gq * 4 + 3]);
+      }
     if (EPI == kEpiStore) {
       constexpr int CPR = ECOLS / 4, RPI = 64 / CPR;   // lanes per row, rows per access
       const int c4 = lane % CPR;
@@ -496,8 +500,8 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
 #pragma unroll
         for (int q = 0; q < DS_HALF; ++q) {
           const int row = (hf * DS_HALF + q) * DS_RPI + lane / DS_CPR;
-          const float4 u0 = *reinterpret_cast<const float4*>(ep + row * EPITCH + ds_c8 * 8);
-          const float4 u1 = *reinterpret_cast<const float4*>(ep + row * EPITCH + ds_c8 * 8 + 4);
+          const float4 u0 = *reinterpret_cast<const float4*>(ep + row * EPITCH + ds_c8 * 4);
+          const float4 u1 = *reinterpret_cast<const float4*>(ep + row * EPITCH + ECOLS / 2 + ds_c8 * 4);
           const int rt = ds_r0 + i * 32 + (hf * DS_HALF + q) * DS_RPI;
           const float rs = g.row_scale[m0 + (rt < ds_rows ? rt : ds_rows - 1)];
           const float u[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w},
