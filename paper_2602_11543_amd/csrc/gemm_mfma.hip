@@ -199,7 +199,11 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   const bf16_t* la_base = nullptr;
   const bf16_t* lb_base = nullptr;
   long l_k0 = 0;
-  int l_step = 0;
+  int l_step = 0, l_kq = 0;                       // l_kq = l_k0 - k_begin
+  const int klen32 = (int)(k_end - k_begin);
+  // row (column of the [k][row] tile) this thread stages of a K-strided operand, clamped into the operand
+  const long a_ks_row = (m0 + (tid % (BM / 8)) * 8 < m_end) ? m0 + (tid % (BM / 8)) * 8 : m0;
+  const long b_ks_row = (n0 + (tid % (BN / 8)) * 8 < g.Ndim) ? n0 + (tid % (BN / 8)) * 8 : n0;
   // gathered k-rows of the tile about to be loaded; fetched one tile ahead so that no load waits on an index
   constexpr int ACH = BM / 8, BCH = BN / 8;     // 16-byte chunks per k-row of a K-strided tile
   int kidx[A_KG ? C::NAS : 1];
@@ -221,9 +225,11 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   auto set_load_tile = [&](int step) {
     const int pass = step / nk;
     l_step = step;
-    l_k0 = k_begin + (long)(step - pass * nk) * BK;
-    la_base = reinterpret_cast<const bf16_t*>(g.A[pass]);
-    lb_base = reinterpret_cast<const bf16_t*>(g.B[(EPI == kEpiSwiglu) ? 0 : pass]) + (B_KC ? 0 : b_group);
+    l_kq = (step - pass * nk) * BK;
+    l_k0 = k_begin + l_kq;
+    // K-strided operands address k relative to the group's first k-row (gathered rows carry absolute indices)
+    la_base = reinterpret_cast<const bf16_t*>(g.A[pass]) + ((A_KC || A_KG) ? 0 : k_begin * g.a_ks);
+    lb_base = reinterpret_cast<const bf16_t*>(g.B[(EPI == kEpiSwiglu) ? 0 : pass]) + (B_KC ? 0 : b_group + k_begin * g.b_ks);
     if (A_KC) {
       a_keep_n = (l_k0 + (tid % CH) * 8 < k_end) ? 0xffu : 0u;
     } else {
@@ -241,11 +247,10 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
       const long k = l_k0 + (tid % CH) * 8;
       ra[idx] = *reinterpret_cast<const uint4*>(la_base + arow[idx] + (a_keep_n ? k : k_begin));
     } else {
-      const long k = l_k0 + tid / ACH + idx * C::KRA;
-      long row = m0 + (tid % ACH) * 8;
-      row = row < m_end ? row : m0;
-      const long kr = A_KG ? (long)kidx[idx] : (k < k_end ? k : k_end - 1);
-      ra[idx] = *reinterpret_cast<const uint4*>(la_base + kr * g.a_ks + row);
+      // 32-bit k relative to the group's first k-row, clamped into the group; one 32 x 32 + 64 multiply-add per address
+      const int kq = l_kq + tid / ACH + idx * C::KRA;
+      const unsigned kr = A_KG ? (unsigned)kidx[idx] : (unsigned)(kq < klen32 ? kq : klen32 - 1);
+      ra[idx] = *reinterpret_cast<const uint4*>(la_base + ((unsigned long)kr * (unsigned)g.a_ks + (unsigned long)a_ks_row));
       if (A_KG && idx == C::NAS - 1) load_kidx(l_step + 1);
     }
   };
@@ -255,11 +260,9 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
       const bf16_t* base = (EPI == kEpiSwiglu && bsecond[idx]) ? reinterpret_cast<const bf16_t*>(g.B[1]) : lb_base;
       rb[idx] = *reinterpret_cast<const uint4*>(base + brow[idx] + (b_keep_n ? k : k_begin));
     } else {
-      const long k = l_k0 + tid / BCH + idx * C::KRB;
-      long row = n0 + (tid % BCH) * 8;
-      row = row < g.Ndim ? row : n0;
-      const long kj = k < k_end ? k : k_end - 1;
-      rb[idx] = *reinterpret_cast<const uint4*>(lb_base + kj * g.b_ks + row);
+      const int kq = l_kq + tid / BCH + idx * C::KRB;
+      const unsigned kj = (unsigned)(kq < klen32 ? kq : klen32 - 1);
+      rb[idx] = *reinterpret_cast<const uint4*>(lb_base + ((unsigned long)kj * (unsigned)g.b_ks + (unsigned long)b_ks_row));
     }
   };
   auto write_a = [&](int stage, int idx) {
