@@ -29,6 +29,8 @@
 // Tiles are enumerated on a 1-D grid and dealt out so that every XCD (workgroups are
 // assigned to the eight XCDs round-robin) gets one contiguous range of tiles: tiles
 // that share an expert's weight panel or a row panel meet in the same L2.
+#include <type_traits>
+
 #include "gemm.h"
 
 namespace spes {
@@ -66,6 +68,8 @@ __device__ __forceinline__ uint4 sel4(bool keep, const uint4& v) {
   const uint32_t m = keep ? 0xffffffffu : 0u;
   return make_uint4(v.x & m, v.y & m, v.z & m, v.w & m);
 }
+// element-wise copy (an aggregate copy of a staging register keeps the whole register array in scratch memory)
+__device__ __forceinline__ uint4 copy4(const uint4& v) { return make_uint4(v.x, v.y, v.z, v.w); }
 __device__ __forceinline__ uint32_t pack2(float a, float b) { return pack_bf16x2(a, b); }
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
@@ -265,29 +269,32 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
       rb[idx] = *reinterpret_cast<const uint4*>(lb_base + ((unsigned long)kj * (unsigned)g.b_ks + (unsigned long)b_ks_row));
     }
   };
-  auto write_a = [&](int stage, int idx) {
+  // `masked`: the tile may reach beyond the contraction range and its k tail is zeroed on the way into LDS.  Only the
+  // last K-tile of a pass can need that; every other tile goes to LDS as it came (the four selects per register are
+  // most of the vector-ALU work of an iteration, and the matrix pipe waits while they issue).
+  auto write_a = [&](int stage, int idx, bool masked) {
     uint4* ta = smem + stage * C::STAGE_VEC;
     if (A_KC) {
-      ta[(tid / CH + RP * idx) * C::PITCH + tid % CH] = sel4(a_keep != 0, ra[idx]);
+      ta[(tid / CH + RP * idx) * C::PITCH + tid % CH] = masked ? sel4(a_keep != 0, ra[idx]) : copy4(ra[idx]);
     } else {
-      ta[(tid / ACH + idx * C::KRA) * C::KPA + tid % ACH] = sel4((a_keep >> idx) & 1u, ra[idx]);
+      ta[(tid / ACH + idx * C::KRA) * C::KPA + tid % ACH] = masked ? sel4((a_keep >> idx) & 1u, ra[idx]) : copy4(ra[idx]);
     }
   };
-  auto write_b = [&](int stage, int idx) {
+  auto write_b = [&](int stage, int idx, bool masked) {
     uint4* tb = smem + stage * C::STAGE_VEC + C::A_VEC;
     if (B_KC) {
-      tb[(tid / CH + RP * idx) * C::PITCH + tid % CH] = sel4(b_keep != 0, rb[idx]);
+      tb[(tid / CH + RP * idx) * C::PITCH + tid % CH] = masked ? sel4(b_keep != 0, rb[idx]) : copy4(rb[idx]);
     } else {
-      tb[(tid / BCH + idx * C::KRB) * C::KPB + tid % BCH] = sel4((b_keep >> idx) & 1u, rb[idx]);
+      tb[(tid / BCH + idx * C::KRB) * C::KPB + tid % BCH] = masked ? sel4((b_keep >> idx) & 1u, rb[idx]) : copy4(rb[idx]);
     }
   };
   // piece p of the pipeline step "tile t+1 to LDS stage `stage`, tile t+2 into registers"
-  auto piece = [&](int p, int stage, bool do_write, bool do_load) {
+  auto piece = [&](int p, int stage, bool do_write, bool do_load, bool masked) {
     if (p < NPA) {
-      if (do_write) write_a(stage, p);
+      if (do_write) write_a(stage, p, masked);
       if (do_load) load_a(p);
     } else {
-      if (do_write) write_b(stage, p - NPA);
+      if (do_write) write_b(stage, p - NPA, masked);
       if (do_load) load_b(p - NPA);
     }
   };
@@ -331,20 +338,22 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
     load_kidx(0);
     set_load_tile(0);
 #pragma unroll
-    for (int p = 0; p < NP; ++p) piece(p, 0, false, true);
+    for (int p = 0; p < NP; ++p) piece(p, 0, false, true, true);
     a_keep = a_keep_n; b_keep = b_keep_n;
     set_load_tile(nsteps > 1 ? 1 : 0);
 #pragma unroll
-    for (int p = 0; p < NP; ++p) piece(p, 0, true, true);
+    for (int p = 0; p < NP; ++p) piece(p, 0, true, true, true);
     a_keep = a_keep_n; b_keep = b_keep_n;
     __syncthreads();
     read_frags(0, 0, 0);
 
     constexpr int MF = TM * TN;                       // MFMAs per k-step
     constexpr int SLOTS = (C::KSTEPS - 1) * MF;       // MFMA slots before the barrier of an iteration
-    for (int t = 0; t < nsteps; ++t) {
-      // no branches in here: past the last K-tile the pipeline keeps running on clamped tiles whose
-      // results are never used (a spare LDS write, a repeated load)
+    // One iteration: MFMAs of K-tile t from LDS stage t&1, K-tile t+1 from registers to the other stage, K-tile t+2
+    // from memory to registers.  No branches in here: past the last K-tile the pipeline keeps running on clamped
+    // tiles whose results are never used (a spare LDS write, a repeated load).
+    auto iteration = [&](int t, auto masked_c) __attribute__((always_inline)) {
+      constexpr bool MASKED = decltype(masked_c)::value;
       const int cur = t & 1;
       set_load_tile(t + 2 < nsteps ? t + 2 : nsteps - 1);
 #pragma unroll
@@ -366,8 +375,8 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
             const int slot = ks * MF + q;
 #pragma unroll
             for (int p = 0; p < NP; ++p) {
-              if (p * SLOTS / NP == slot) piece(p, cur ^ 1, true, false);
-              if (p * SLOTS / NP + 1 == slot) piece(p, cur ^ 1, false, true);
+              if (p * SLOTS / NP == slot) piece(p, cur ^ 1, true, false, MASKED);
+              if (p * SLOTS / NP + 1 == slot) piece(p, cur ^ 1, false, true, MASKED);
             }
           }
           __builtin_amdgcn_sched_barrier(0);
@@ -377,6 +386,18 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
           __syncthreads();
         }
       }
+    };
+    // The body exists twice: an inner loop without the k-tail selects for the tiles in the middle of a pass, and one
+    // straight-line copy with them for the iteration that writes the last tile of a pass (and for the final iteration,
+    // whose write is the spare one).  w = t + 1 is the tile written in iteration t.
+    int w = 1, pass_end = nk - 1;
+    while (true) {
+      const int stop = pass_end < nsteps ? pass_end : nsteps;
+      for (; w < stop; ++w) iteration(w - 1, std::false_type{});
+      iteration(w - 1, std::true_type{});
+      ++w;
+      pass_end += nk;
+      if (w > nsteps) break;
     }
   }
 
