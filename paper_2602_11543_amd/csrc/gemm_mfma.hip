@@ -369,8 +369,8 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
           // everything else is dealt out over the gaps between MFMAs in portions that fit under one MFMA:
           // one fragment read of the next k-step every FR-th gap, and per staging register its LDS write in
           // one gap and its reload in the next
-          constexpr int FR = MF / (TM + TN);
-          if (q % FR == 0) read_frag(nstage, nks, set ^ 1, q / FR);
+          constexpr int FR = MF / (TM + TN) > 0 ? MF / (TM + TN) : 1;
+          if (q % FR == 0 && q / FR < TM + TN) read_frag(nstage, nks, set ^ 1, q / FR);
           if (ks < C::KSTEPS - 1) {
             const int slot = ks * MF + q;
 #pragma unroll
