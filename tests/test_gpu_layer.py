@@ -47,6 +47,15 @@ def test_layer_parity(name, device):
     dict(T=200, d=64, M=8, f=64, k=1, bias="normal", bias_scale=8.0),    # nearly every token to one expert, several empty
     dict(T=333, d=264, M=16, f=200, k=4, renorm=1, dtype="bf16", n_trainable=5, trainable="random", router_sigma=0.05),
     dict(T=96, d=64, M=8, f=64, k=2, n_trainable=0),                    # nothing trainable: no weight-grad buffers at all
+    # the same corners through the matrix-core path (bf16): contraction lengths of one and two K-tiles with and
+    # without a tail, two passes of one tile each, experts with fewer rows than one k-tile or none at all
+    dict(T=1, d=64, M=4, f=64, k=2, dtype="bf16"),
+    dict(T=67, d=72, M=1, f=40, k=1, n_trainable=1, dtype="bf16"),
+    dict(T=130, d=64, M=6, f=56, k=6, n_trainable=3, dtype="bf16"),
+    dict(T=257, d=136, M=64, f=72, k=3, n_trainable=7, trainable="random", dtype="bf16"),
+    dict(T=200, d=128, M=8, f=128, k=1, bias="normal", bias_scale=8.0, dtype="bf16"),
+    dict(T=96, d=8, M=8, f=8, k=2, n_trainable=8, dtype="bf16"),        # the smallest feature sizes the library takes
+    dict(T=300, d=192, M=12, f=320, k=2, renorm=1, n_trainable=0, dtype="bf16"),
 ])
 def test_layer_edge_cases(kw, device):
     kw = dict(kw); kw.setdefault("router_sigma", 0.3)
