@@ -220,10 +220,11 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
     }
   };
   // registers 0..n-1 of a K-strided operand hold k-rows inside the contraction range
-  auto keep_bits = [&](long first_k, int rows_per_pass, int nreg) -> unsigned {
-    const long left = k_end - first_k;
-    long n = (left + rows_per_pass - 1) / rows_per_pass;
-    n = n < 0 ? 0 : n > nreg ? nreg : n;
+  // (first_kq = k of the thread's first register relative to the group; rows_per_pass is a power of two)
+  auto keep_bits = [&](int first_kq, int rows_per_pass, int nreg) -> unsigned {
+    const int left = klen32 - first_kq;
+    int n = (left + rows_per_pass - 1) >> __builtin_ctz(rows_per_pass);      // arithmetic shift: negative stays negative
+    n = max(0, min(n, nreg));
     return (1u << n) - 1u;
   };
   auto set_load_tile = [&](int step) {
@@ -235,21 +236,21 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
     la_base = reinterpret_cast<const bf16_t*>(g.A[pass]) + ((A_KC || A_KG) ? 0 : k_begin * g.a_ks);
     lb_base = reinterpret_cast<const bf16_t*>(g.B[(EPI == kEpiSwiglu) ? 0 : pass]) + (B_KC ? 0 : b_group + k_begin * g.b_ks);
     if (A_KC) {
-      a_keep_n = (l_k0 + (tid % CH) * 8 < k_end) ? 0xffu : 0u;
+      a_keep_n = (l_kq + (tid % CH) * 8 < klen32) ? 0xffu : 0u;
     } else {
-      a_keep_n = keep_bits(l_k0 + tid / ACH, C::KRA, C::NAS);
+      a_keep_n = keep_bits(l_kq + tid / ACH, C::KRA, C::NAS);
     }
     if (B_KC) {
-      b_keep_n = (l_k0 + (tid % CH) * 8 < k_end) ? 0xffu : 0u;
+      b_keep_n = (l_kq + (tid % CH) * 8 < klen32) ? 0xffu : 0u;
     } else {
-      b_keep_n = keep_bits(l_k0 + tid / BCH, C::KRB, C::NBS);
+      b_keep_n = keep_bits(l_kq + tid / BCH, C::KRB, C::NBS);
     }
   };
 
   auto load_a = [&](int idx) {   // idx: staging register
     if (A_KC) {
-      const long k = l_k0 + (tid % CH) * 8;
-      ra[idx] = *reinterpret_cast<const uint4*>(la_base + arow[idx] + (a_keep_n ? k : k_begin));
+      const int kq = a_keep_n ? l_kq + (tid % CH) * 8 : 0;        // a chunk beyond the range reads the row's first chunk instead
+      ra[idx] = *reinterpret_cast<const uint4*>(la_base + k_begin + arow[idx] + kq);
     } else {
       // 32-bit k relative to the group's first k-row, clamped into the group; one 32 x 32 + 64 multiply-add per address
       const int kq = l_kq + tid / ACH + idx * C::KRA;
@@ -260,9 +261,9 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   };
   auto load_b = [&](int idx) {
     if (B_KC) {
-      const long k = l_k0 + (tid % CH) * 8;
+      const int kq = b_keep_n ? l_kq + (tid % CH) * 8 : 0;
       const bf16_t* base = (EPI == kEpiSwiglu && bsecond[idx]) ? reinterpret_cast<const bf16_t*>(g.B[1]) : lb_base;
-      rb[idx] = *reinterpret_cast<const uint4*>(base + brow[idx] + (b_keep_n ? k : k_begin));
+      rb[idx] = *reinterpret_cast<const uint4*>(base + k_begin + brow[idx] + kq);
     } else {
       const int kq = l_kq + tid / BCH + idx * C::KRB;
       const unsigned kj = (unsigned)(kq < klen32 ? kq : klen32 - 1);
