@@ -163,8 +163,8 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
   // router scores: logits[T,M] = x W_r^T
   {
     GemmArgs g = blank();
-    g.A[0] = x; g.a_ms = d; g.a_ks = 1;
-    g.B[0] = w_router; g.b_ns = d; g.b_ks = 1;
+    g.A[0] = x; g.a_ms = d; g.a_ks = 1; g.a_elems = (long)T * d;
+    g.B[0] = w_router; g.b_ns = d; g.b_ks = 1; g.b_elems = (long)M * d;
     g.Kdim = d; g.kchunk = d; g.Mdim = T; g.Ndim = M;
     g.C[0] = at<float>(ctx, L.pub.logits); g.c_ms = M; g.c_f32 = 1;
     // the matrix-core epilogue stores four columns at a time; with only M <= 64 output columns the row tiles alone
@@ -192,8 +192,8 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
   // a = xp W_g^T, b = xp W_u^T, h = SiLU(a) * b
   {
     GemmArgs g = blank();
-    g.A[0] = at<void>(ctx, L.pub.xp); g.a_ms = d; g.a_ks = 1;
-    g.B[0] = w_gate; g.B[1] = w_up; g.b_ns = d; g.b_ks = 1; g.b_gs = (long)f * d;
+    g.A[0] = at<void>(ctx, L.pub.xp); g.a_ms = d; g.a_ks = 1; g.a_elems = R * d;
+    g.B[0] = w_gate; g.B[1] = w_up; g.b_ns = d; g.b_ks = 1; g.b_gs = (long)f * d; g.b_elems = (long)M * f * d;
     g.Kdim = d; g.Ndim = f;
     g.C[0] = at<void>(ctx, L.pub.a); g.C[1] = at<void>(ctx, L.pub.b); g.C[2] = at<void>(ctx, L.pub.h); g.c_ms = f;
     ragged_tables(g, ctx, L, dt);
@@ -203,8 +203,8 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
   // yp = h W_d^T
   {
     GemmArgs g = blank();
-    g.A[0] = at<void>(ctx, L.pub.h); g.a_ms = f; g.a_ks = 1;
-    g.B[0] = w_down; g.b_ns = f; g.b_ks = 1; g.b_gs = (long)d * f;
+    g.A[0] = at<void>(ctx, L.pub.h); g.a_ms = f; g.a_ks = 1; g.a_elems = R * f;
+    g.B[0] = w_down; g.b_ns = f; g.b_ks = 1; g.b_gs = (long)d * f; g.b_elems = (long)M * d * f;
     g.Kdim = f; g.Ndim = d;
     g.C[0] = at<void>(ctx, L.pub.yp); g.c_ms = d;
     ragged_tables(g, ctx, L, dt);
@@ -259,8 +259,8 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
   prof_begin(1, s);
   {
     GemmArgs g = blank();
-    g.A[0] = dy; g.a_ms = d; g.a_ks = 1; g.a_rows = at<int>(ctx, L.row_token);
-    g.B[0] = w_down; g.b_ns = 1; g.b_ks = f; g.b_gs = (long)d * f;
+    g.A[0] = dy; g.a_ms = d; g.a_ks = 1; g.a_rows = at<int>(ctx, L.row_token); g.a_elems = (long)T * d;
+    g.B[0] = w_down; g.b_ns = 1; g.b_ks = f; g.b_gs = (long)d * f; g.b_elems = (long)M * d * f;
     g.Kdim = d; g.Ndim = f;
     g.E[0] = at<void>(ctx, L.pub.a); g.E[1] = at<void>(ctx, L.pub.b);
     g.C[0] = at<void>(ctx, L.da); g.C[1] = at<void>(ctx, L.db); g.C[2] = at<void>(ctx, L.hg); g.c_ms = f;
@@ -278,8 +278,8 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
   {
     GemmArgs g = blank();
     g.npairs = 2;
-    g.A[0] = at<void>(ctx, L.da); g.A[1] = at<void>(ctx, L.db); g.a_ms = f; g.a_ks = 1;
-    g.B[0] = w_gate; g.B[1] = w_up; g.b_ns = 1; g.b_ks = d; g.b_gs = (long)f * d;
+    g.A[0] = at<void>(ctx, L.da); g.A[1] = at<void>(ctx, L.db); g.a_ms = f; g.a_ks = 1; g.a_elems = R * f;
+    g.B[0] = w_gate; g.B[1] = w_up; g.b_ns = 1; g.b_ks = d; g.b_gs = (long)f * d; g.b_elems = (long)M * f * d;
     g.Kdim = f; g.Ndim = d;
     g.C[0] = at<void>(ctx, L.dxp); g.c_ms = d;
     ragged_tables(g, ctx, L, dt);
@@ -294,14 +294,14 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
     g.offset = at<int>(ctx, L.pub.offset);
     g.c_f32 = 1; g.accumulate = accumulate;
     // dW_d[d,f] = dy[token]^T (gate * h) over the expert's rows
-    g.A[0] = dy; g.a_ms = 1; g.a_ks = d; g.a_rows = at<int>(ctx, L.row_token);
-    g.B[0] = at<void>(ctx, L.hg); g.b_ns = 1; g.b_ks = f;
+    g.A[0] = dy; g.a_ms = 1; g.a_ks = d; g.a_rows = at<int>(ctx, L.row_token); g.a_elems = (long)T * d;
+    g.B[0] = at<void>(ctx, L.hg); g.b_ns = 1; g.b_ks = f; g.b_elems = R * f;
     g.Mdim = d; g.Ndim = f; g.C[0] = d_w_down; g.c_ms = f; g.c_gs = (long)d * f;
     SPES_TRY(expert_gemm(dt, kGroupedK, kEpiStore, false, false, g, s));
     prof_mark(1, "wgrad_down", s);
     // dW_g[f,d] = da^T xp ; dW_u[f,d] = db^T xp
-    g.B[0] = at<void>(ctx, L.pub.xp); g.b_ns = 1; g.b_ks = d;
-    g.a_ms = 1; g.a_ks = f; g.a_rows = nullptr; g.Mdim = f; g.Ndim = d; g.c_ms = d; g.c_gs = (long)f * d;
+    g.B[0] = at<void>(ctx, L.pub.xp); g.b_ns = 1; g.b_ks = d; g.b_elems = R * d;
+    g.a_ms = 1; g.a_ks = f; g.a_rows = nullptr; g.a_elems = R * f; g.Mdim = f; g.Ndim = d; g.c_ms = d; g.c_gs = (long)f * d;
     g.A[0] = at<void>(ctx, L.da); g.C[0] = d_w_gate;
     SPES_TRY(expert_gemm(dt, kGroupedK, kEpiStore, false, false, g, s));
     prof_mark(1, "wgrad_gate", s);
@@ -312,8 +312,8 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
   // dW_r[M,d] = dlogits^T x; the token axis is cut into chunks whose partial products are then added in a fixed order
   {
     GemmArgs g = blank();
-    g.a_ms = 1; g.a_ks = M;
-    g.B[0] = x; g.b_ns = 1; g.b_ks = d;
+    g.a_ms = 1; g.a_ks = M; g.a_elems = (long)T * M;
+    g.B[0] = x; g.b_ns = 1; g.b_ks = d; g.b_elems = (long)T * d;
     g.Kdim = T; g.Mdim = M; g.Ndim = d;
     g.C[0] = at<float>(ctx, L.wr_part); g.c_ms = d; g.c_gs = (long)M * d; g.c_f32 = 1;
     if (router_mfma) {
@@ -331,8 +331,8 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
   // router part of the input gradient, dxr[T,d] = dlogits W_r, as its own small GEMM in bf16 mode
   if (router_mfma) {
     GemmArgs g = blank();
-    g.A[0] = at<void>(ctx, L.dlogits_bf); g.a_ms = M; g.a_ks = 1;
-    g.B[0] = w_router; g.b_ns = 1; g.b_ks = d;
+    g.A[0] = at<void>(ctx, L.dlogits_bf); g.a_ms = M; g.a_ks = 1; g.a_elems = (long)T * M;
+    g.B[0] = w_router; g.b_ns = 1; g.b_ks = d; g.b_elems = (long)M * d;
     g.Kdim = M; g.kchunk = (M + 63) / 64 * 64; g.Mdim = T; g.Ndim = d;
     g.C[0] = at<void>(ctx, L.dxr); g.c_ms = d;
     SPES_TRY(launch_gemm_mfma(kGroupedK, kEpiStore, true, false, g, s));
@@ -438,8 +438,8 @@ SPES_API int spes_expert_warmup_merge(int32_t n_experts, int32_t dtype, int32_t 
   {
     // Gram matrix of the flattened input projections, split along the long contraction
     GemmArgs g = blank();
-    g.A[0] = w_in; g.a_ms = elems_in; g.a_ks = 1;
-    g.B[0] = w_in; g.b_ns = elems_in; g.b_ks = 1;
+    g.A[0] = w_in; g.a_ms = elems_in; g.a_ks = 1; g.a_elems = (long)n_experts * elems_in;
+    g.B[0] = w_in; g.b_ns = elems_in; g.b_ks = 1; g.b_elems = (long)n_experts * elems_in;
     g.Kdim = (int)elems_in; g.kchunk = (int)kchunk; g.n_groups = ng;
     g.Mdim = M; g.Ndim = M;
     g.C[0] = scratch; g.c_ms = M; g.c_gs = (long)M * M; g.c_f32 = 1;

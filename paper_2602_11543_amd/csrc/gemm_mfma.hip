@@ -19,8 +19,11 @@
 // order in LDS, [k][row] with a pitch of rows*2+64 bytes: it is loaded in 512-byte
 // runs along a k-row, and the MFMA fragments (eight consecutive k of one row per lane)
 // come out of LDS through the transposing read ds_read_b64_tr_b16, four k at a time.
-// Loads are unconditional: rows and k beyond the operand are clamped to valid
-// addresses, the k tail is zeroed by select, surplus rows are never stored.
+// Operands are read through buffer resources (uniform base and byte count, a per-lane
+// 32-bit offset fixed for the whole tile, a uniform offset that moves with the K-tile):
+// the loop computes no addresses, and loads are unconditional - a read beyond the tensor
+// returns zero, a read beyond the tile returns data that is never used (the k tail is
+// zeroed by select on its way into LDS, surplus rows are never stored).
 //
 // The MFMA operands are swapped (weights tile as the "A" input) so that each lane ends
 // up holding runs of four consecutive output columns of one row: epilogues then work
@@ -71,6 +74,18 @@ __device__ __forceinline__ uint4 sel4(bool keep, const uint4& v) {
 // element-wise copy (an aggregate copy of a staging register keeps the whole register array in scratch memory)
 __device__ __forceinline__ uint4 copy4(const uint4& v) { return make_uint4(v.x, v.y, v.z, v.w); }
 __device__ __forceinline__ uint32_t pack2(float a, float b) { return pack_bf16x2(a, b); }
+
+// raw buffer resource over `bytes` bytes from `base`; loads at byte offsets at or beyond `bytes` return zero
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+// 16 bytes at base + lane_off + uniform_off
+__device__ __forceinline__ uint4 buffer_load16(rsrc_t rs, unsigned lane_off, unsigned uniform_off) {
+  const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)lane_off, (int)uniform_off, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
@@ -143,34 +158,35 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   }
   const long n0 = (long)nt * BNO;
 
-  // ---- K-contiguous operands: source row of each staged tile row (clamped into the operand) ----
-  long arow[A_KC ? C::NA : 1];
-  long brow[B_KC ? C::NB : 1];
-  bool bsecond[B_KC ? C::NB : 1];   // fused SwiGLU: the row comes from the second matrix
+  // ---- operands are read through buffer resources: a base (uniform) with a byte count, a 32-bit byte offset per
+  // lane that is fixed for the whole tile, and a uniform offset that moves with the K-tile.  Nothing in the loop
+  // computes an address, and no clamp is needed for memory safety: a read inside the tensor but outside the tile
+  // returns data that is never used (masked k tail, rows that are not stored), a read beyond the tensor returns zero.
+  const unsigned a_bytes = (unsigned)(g.a_elems * 2), b_bytes = (unsigned)((g.b_elems - b_group) * 2);
+  const rsrc_t a_rsrc[2] = {make_rsrc(g.A[0], a_bytes), make_rsrc(g.A[1] ? g.A[1] : g.A[0], a_bytes)};
+  const rsrc_t b_rsrc[2] = {make_rsrc(reinterpret_cast<const bf16_t*>(g.B[0]) + b_group, b_bytes),
+                            make_rsrc(reinterpret_cast<const bf16_t*>(g.B[1] ? g.B[1] : g.B[0]) + b_group, b_bytes)};
+  // K-contiguous operands: byte offset of this thread's chunk in K-tile 0, per staging register
+  unsigned aoff[A_KC ? C::NA : 1];
+  unsigned boff[B_KC ? C::NB : 1];
   if (A_KC) {
 #pragma unroll
     for (int i = 0; i < C::NA; ++i) {
       long m = m0 + tid / CH + RP * i;
-      m = m < m_end ? m : m_end - 1;
-      arow[i] = ((MODE == kRaggedM && g.a_rows) ? (long)g.a_rows[m] : m) * g.a_ms;
+      if (MODE == kRaggedM && g.a_rows) m = g.a_rows[m < m_end ? m : m_end - 1];       // the index table is only that long
+      aoff[i] = (unsigned)((m * g.a_ms + (tid % CH) * 8) * 2);
     }
   }
+  // fused SwiGLU: staging register i holds rows of the gate matrix (B[0]) or of the up matrix (B[1]); tile row nl ->
+  // wave column, then (BN/4) gate columns followed by the matching (BN/4) up columns
+  constexpr int SW_W = BN / 2, SW_H = BN / 4;
+  static_assert(EPI != kEpiSwiglu || (SW_H % RP == 0), "a staging register must not straddle the gate / up boundary");
   if (B_KC) {
 #pragma unroll
     for (int i = 0; i < C::NB; ++i) {
       const int nl = tid / CH + RP * i;
-      long col;
-      bsecond[i] = false;
-      if (EPI == kEpiSwiglu) {
-        // tile row nl -> wave column, then (BN/4) gate columns followed by the matching (BN/4) up columns
-        constexpr int W = BN / 2, H = BN / 4;
-        col = n0 + (nl / W) * H + (nl % H);
-        bsecond[i] = ((nl % W) / H) != 0;
-      } else {
-        col = n0 + nl;
-      }
-      col = col < g.Ndim ? col : g.Ndim - 1;
-      brow[i] = b_group + col * g.b_ns;
+      const long col = (EPI == kEpiSwiglu) ? n0 + (nl / SW_W) * SW_H + (nl % SW_H) : n0 + nl;
+      boff[i] = (unsigned)((col * g.b_ns + (tid % CH) * 8) * 2);
     }
   }
 
@@ -200,14 +216,11 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   constexpr int NP = NPA + NPB;
 
   // scalar coordinates of the K-tile being loaded
-  const bf16_t* la_base = nullptr;
-  const bf16_t* lb_base = nullptr;
-  long l_k0 = 0;
-  int l_step = 0, l_kq = 0;                       // l_kq = l_k0 - k_begin
+  int l_step = 0, l_kq = 0, l_pass = 0;           // tile number, k of the tile relative to the group, pass
   const int klen32 = (int)(k_end - k_begin);
-  // row (column of the [k][row] tile) this thread stages of a K-strided operand, clamped into the operand
-  const long a_ks_row = (m0 + (tid % (BM / 8)) * 8 < m_end) ? m0 + (tid % (BM / 8)) * 8 : m0;
-  const long b_ks_row = (n0 + (tid % (BN / 8)) * 8 < g.Ndim) ? n0 + (tid % (BN / 8)) * 8 : n0;
+  // K-strided operands: byte offset of this thread's chunk in k-row 0 of K-tile 0
+  const unsigned a_ks_off = (unsigned)(((long)(tid / (BM / 8)) * g.a_ks + m0 + (tid % (BM / 8)) * 8) * 2);
+  const unsigned b_ks_off = (unsigned)(((long)(tid / (BN / 8)) * g.b_ks + n0 + (tid % (BN / 8)) * 8) * 2);
   // gathered k-rows of the tile about to be loaded; fetched one tile ahead so that no load waits on an index
   constexpr int ACH = BM / 8, BCH = BN / 8;     // 16-byte chunks per k-row of a K-strided tile
   int kidx[A_KG ? C::NAS : 1];
@@ -228,13 +241,9 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
     return (1u << n) - 1u;
   };
   auto set_load_tile = [&](int step) {
-    const int pass = step / nk;
+    l_pass = step / nk;
     l_step = step;
-    l_kq = (step - pass * nk) * BK;
-    l_k0 = k_begin + l_kq;
-    // K-strided operands address k relative to the group's first k-row (gathered rows carry absolute indices)
-    la_base = reinterpret_cast<const bf16_t*>(g.A[pass]) + ((A_KC || A_KG) ? 0 : k_begin * g.a_ks);
-    lb_base = reinterpret_cast<const bf16_t*>(g.B[(EPI == kEpiSwiglu) ? 0 : pass]) + (B_KC ? 0 : b_group + k_begin * g.b_ks);
+    l_kq = (step - l_pass * nk) * BK;
     if (A_KC) {
       a_keep_n = (l_kq + (tid % CH) * 8 < klen32) ? 0xffu : 0u;
     } else {
@@ -248,26 +257,23 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   };
 
   auto load_a = [&](int idx) {   // idx: staging register
+    const rsrc_t rs = l_pass ? a_rsrc[1] : a_rsrc[0];
     if (A_KC) {
-      const int kq = a_keep_n ? l_kq + (tid % CH) * 8 : 0;        // a chunk beyond the range reads the row's first chunk instead
-      ra[idx] = *reinterpret_cast<const uint4*>(la_base + k_begin + arow[idx] + kq);
+      ra[idx] = buffer_load16(rs, aoff[idx], (unsigned)((k_begin + l_kq) * 2));
+    } else if (A_KG) {
+      ra[idx] = buffer_load16(rs, (unsigned)kidx[idx] * (unsigned)(g.a_ks * 2) + (unsigned)((m0 + (tid % ACH) * 8) * 2), 0u);
+      if (idx == C::NAS - 1) load_kidx(l_step + 1);
     } else {
-      // 32-bit k relative to the group's first k-row, clamped into the group; one 32 x 32 + 64 multiply-add per address
-      const int kq = l_kq + tid / ACH + idx * C::KRA;
-      const unsigned kr = A_KG ? (unsigned)kidx[idx] : (unsigned)(kq < klen32 ? kq : klen32 - 1);
-      ra[idx] = *reinterpret_cast<const uint4*>(la_base + ((unsigned long)kr * (unsigned)g.a_ks + (unsigned long)a_ks_row));
-      if (A_KG && idx == C::NAS - 1) load_kidx(l_step + 1);
+      ra[idx] = buffer_load16(rs, a_ks_off, (unsigned)((k_begin + l_kq + idx * C::KRA) * g.a_ks * 2));
     }
   };
   auto load_b = [&](int idx) {
     if (B_KC) {
-      const int kq = b_keep_n ? l_kq + (tid % CH) * 8 : 0;
-      const bf16_t* base = (EPI == kEpiSwiglu && bsecond[idx]) ? reinterpret_cast<const bf16_t*>(g.B[1]) : lb_base;
-      rb[idx] = *reinterpret_cast<const uint4*>(base + k_begin + brow[idx] + kq);
+      // (the register -> matrix assignment of the fused SwiGLU is the same for every thread)
+      const bool second = (EPI == kEpiSwiglu) ? (((RP * idx) % SW_W) / SW_H) != 0 : l_pass != 0;
+      rb[idx] = buffer_load16(second ? b_rsrc[1] : b_rsrc[0], boff[idx], (unsigned)((k_begin + l_kq) * 2));
     } else {
-      const int kq = l_kq + tid / BCH + idx * C::KRB;
-      const unsigned kj = (unsigned)(kq < klen32 ? kq : klen32 - 1);
-      rb[idx] = *reinterpret_cast<const uint4*>(lb_base + ((unsigned long)kj * (unsigned)g.b_ks + (unsigned long)b_ks_row));
+      rb[idx] = buffer_load16(l_pass ? b_rsrc[1] : b_rsrc[0], b_ks_off, (unsigned)((k_begin + l_kq + idx * C::KRB) * g.b_ks * 2));
     }
   };
   // `masked`: the tile may reach beyond the contraction range and its k tail is zeroed on the way into LDS.  Only the
@@ -583,6 +589,9 @@ template <int MODE, int EPI, bool A_KC, bool B_KC, bool A_KG = false>
 int launch(const GemmArgs& g, hipStream_t s) {
   typedef Tile C;
   static_assert(!A_KG || !A_KC, "k-row gather: K-strided A only");
+  // operands are addressed with 32-bit byte offsets from their base
+  if (g.a_elems <= 0 || g.b_elems <= 0) return SPES_EINVAL;
+  if (g.a_elems >= (1L << 31) || g.b_elems >= (1L << 31)) return SPES_ESHAPE;
   const int bno = (EPI == kEpiSwiglu) ? C::BN / 2 : C::BN;
   const int gx = cdiv(g.Ndim, bno);
   long total = (MODE == kRaggedM) ? (long)g.max_tiles * gx : (long)g.n_groups * cdiv(g.Mdim, C::BM) * gx;
