@@ -415,7 +415,11 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   // 256 to 512 contiguous bytes per row.
   constexpr int ECOLS = TN * 32, EPITCH = ECOLS + 4; // floats per LDS row (pitch keeps the writes conflict-free)
   float* ep = reinterpret_cast<float*>(smem) + wave * (32 * EPITCH);
-  const long m_base = m0 + wm * (BM / 2);
+  // output addresses are a per-tile base (uniform) plus a 32-bit element offset: row within the tile times the row
+  // stride plus the column; rows are compared with the tile's valid row count in 32 bits as well
+  const int e_rows = (int)(m_end - m0);
+  const long e_tile = c_group + m0 * g.c_ms;
+  const int e_r0 = wm * (BM / 2);
   // dSwiGLU epilogue: lanes lie along the columns (DS_CPR lanes per row, eight columns each, so that the bf16
   // results leave in 16-byte stores); the saved fp32 projections come in batches of half a 32-row slab
   constexpr int DS_CPR = ECOLS / 8, DS_RPI = 64 / DS_CPR, DS_NB = 2, DS_HALF = 32 / DS_RPI / DS_NB;
@@ -464,14 +468,16 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
       constexpr int CPR = ECOLS / 8, RPI = 64 / CPR;   // lanes per row (eight columns each), rows per access
       const int c8 = lane % CPR;
       const long n = n0 + wn * (BN / 2) + c8 * 8;
+      const bool n_in = n < g.Ndim;
+      bf16_t* ct = reinterpret_cast<bf16_t*>(g.C[0]) + e_tile;
 #pragma unroll
       for (int st = 0; st < 32 / RPI; ++st) {
         const int row = st * RPI + lane / CPR;
         const uint2 lo = *reinterpret_cast<const uint2*>(eb + row * BPITCH + c8 * 16);
         const uint2 hi = *reinterpret_cast<const uint2*>(eb + row * BPITCH + c8 * 16 + 8);
-        const long m = m_base + i * 32 + row;
-        if (m < m_end && n < g.Ndim)
-          *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(g.C[0]) + c_group + m * g.c_ms + n) = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        const int rt = e_r0 + i * 32 + row;
+        if (rt < e_rows && n_in)
+          *reinterpret_cast<uint4*>(ct + ((unsigned)rt * (unsigned)g.c_ms + (unsigned)n)) = make_uint4(lo.x, lo.y, hi.x, hi.y);
       }
       continue;
     }
@@ -489,13 +495,15 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
       constexpr int CPR = ECOLS / 4, RPI = 64 / CPR;   // lanes per row, rows per access
       const int c4 = lane % CPR;
       const long n = n0 + wn * (BN / 2) + c4 * 4;
+      const bool n_in = n < g.Ndim;
+      float* ct = reinterpret_cast<float*>(g.C[0]) + e_tile;
 #pragma unroll
       for (int st = 0; st < 32 / RPI; ++st) {
         const int row = st * RPI + lane / CPR;
         const float4 v = *reinterpret_cast<const float4*>(ep + row * EPITCH + c4 * 4);
-        const long m = m_base + i * 32 + row;
-        if (m < m_end && n < g.Ndim) {
-          float4* c = reinterpret_cast<float4*>(reinterpret_cast<float*>(g.C[0]) + c_group + m * g.c_ms + n);
+        const int rt = e_r0 + i * 32 + row;
+        if (rt < e_rows && n_in) {
+          float4* c = reinterpret_cast<float4*>(ct + ((unsigned)rt * (unsigned)g.c_ms + (unsigned)n));
           float4 o = v;
           if (g.accumulate) { const float4 old = *c; o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w; }
           *c = o;
@@ -506,21 +514,25 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
       constexpr int CPR = ECOLS / 8, RPI = 64 / CPR;
       const int c4 = lane % CPR;
       const long n = n0 + wn * (BN / 4) + c4 * 4;
+      const bool n_in = n < g.Ndim;
+      float* cat = reinterpret_cast<float*>(g.C[0]) + e_tile;
+      float* cbt = reinterpret_cast<float*>(g.C[1]) + e_tile;
+      bf16_t* cht = reinterpret_cast<bf16_t*>(g.C[2]) + e_tile;
 #pragma unroll
       for (int st = 0; st < 32 / RPI; ++st) {
         const int row = st * RPI + lane / CPR;
         const float4 av = *reinterpret_cast<const float4*>(ep + row * EPITCH + c4 * 4);
         const float4 bv = *reinterpret_cast<const float4*>(ep + row * EPITCH + ECOLS / 2 + c4 * 4);
-        const long m = m_base + i * 32 + row;
-        if (m < m_end && n < g.Ndim) {
-          const long ci = m * g.c_ms + n;
+        const int rt = e_r0 + i * 32 + row;
+        if (rt < e_rows && n_in) {
+          const unsigned ci = (unsigned)rt * (unsigned)g.c_ms + (unsigned)n;
           const float a[4] = {av.x, av.y, av.z, av.w}, b[4] = {bv.x, bv.y, bv.z, bv.w};
           float h[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) h[e] = a[e] * sigmoidf_(a[e]) * b[e];
-          *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.C[0]) + ci) = av;
-          *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.C[1]) + ci) = bv;
-          *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.C[2]) + ci) = make_uint2(pack2(h[0], h[1]), pack2(h[2], h[3]));
+          *reinterpret_cast<float4*>(cat + ci) = av;
+          *reinterpret_cast<float4*>(cbt + ci) = bv;
+          *reinterpret_cast<uint2*>(cht + ci) = make_uint2(pack2(h[0], h[1]), pack2(h[2], h[3]));
         }
       }
     } else {
