@@ -266,6 +266,9 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
     g.C[0] = at<void>(ctx, L.da); g.C[1] = at<void>(ctx, L.db); g.C[2] = at<void>(ctx, L.hg); g.c_ms = f;
     g.row_scale = at<float>(ctx, L.row_gate);
     g.rowdot = at<float>(ctx, L.dgate_part); g.rowdot_stride = R;
+    // gate * h feeds only the down-projection weight gradient, which exists for the trainable experts alone
+    for (int e = 0; e < M; ++e)
+      if (!trainable_mask[e]) g.c2_skip |= 1ull << e;
     ragged_tables(g, ctx, L, dt);
     SPES_TRY(expert_gemm(dt, kRaggedM, kEpiDSwiglu, true, false, g, s));
   }

@@ -48,6 +48,7 @@ struct GemmArgs {
   const int* n_tiles;
   const int* offset;      // [M+1] first routed row of each expert
   int max_tiles;
+  unsigned long long c2_skip;  // kEpiDSwiglu: bit e set = nothing reads C[2] for expert e's rows; the matrix-core path leaves them unwritten
   // kGroupedK
   int n_groups;
   int kchunk;             // offset == nullptr: group g contracts k in [g*kchunk, min(Kdim,(g+1)*kchunk))

@@ -127,8 +127,10 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   const long mt_all = logical / gx;
 
   long m0, m_end, k_begin, k_end, b_group = 0, c_group = 0;
+  bool ds_store2 = true;
   if (MODE == kRaggedM) {
     const int e = g.tile_expert[mt_all];
+    ds_store2 = ((g.c2_skip >> e) & 1ull) == 0;
     m0 = g.tile_row0[mt_all];
     m_end = min((long)g.offset[e + 1], m0 + BM);
     k_begin = 0; k_end = g.Kdim;
@@ -585,7 +587,7 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
             const unsigned ci = (unsigned)rt * (unsigned)g.c_ms + ds_ncl;
             *reinterpret_cast<uint4*>(ds_c0 + ci) = oa[q];
             *reinterpret_cast<uint4*>(ds_c1 + ci) = ob[q];
-            *reinterpret_cast<uint4*>(ds_c2 + ci) = oh[q];
+            if (ds_store2) *reinterpret_cast<uint4*>(ds_c2 + ci) = oh[q];
           }
           if (ds_c8 == 0 && rt < ds_rows) g.rowdot[(long)(nt * 2 + wn) * g.rowdot_stride + m0 + rt] = dots[q];
         }
