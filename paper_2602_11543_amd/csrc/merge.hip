@@ -30,7 +30,7 @@ __global__ __launch_bounds__(256) void sync_merge_kernel(const MergeTable tb, T*
   const long stride = (long)gridDim.x * 256;
   for (long v = (long)blockIdx.x * 256 + threadIdx.x; v < nvec; v += stride) {
     Vec16<T> q;
-    q.load(reinterpret_cast<const T*>(tb.src[b]) + v * N);
+    q.load_once(reinterpret_cast<const T*>(tb.src[b]) + v * N);
     if (n > 1) {
       float f0[N], acc[N];
       q.unpack(f0);
@@ -38,7 +38,7 @@ __global__ __launch_bounds__(256) void sync_merge_kernel(const MergeTable tb, T*
       for (int i = 0; i < N; ++i) acc[i] = f0[i];
       for (int s = 1; s < n; ++s) {
         Vec16<T> qs;
-        qs.load(reinterpret_cast<const T*>(tb.src[b + s]) + v * N);
+        qs.load_once(reinterpret_cast<const T*>(tb.src[b + s]) + v * N);
         float f[N];
         qs.unpack(f);
         const float w = tb.w[b + s];
@@ -47,7 +47,7 @@ __global__ __launch_bounds__(256) void sync_merge_kernel(const MergeTable tb, T*
       }
       q.pack(acc);
     }
-    q.store(out + v * N);
+    q.store_once(out + v * N);
   }
 }
 
@@ -123,7 +123,7 @@ __global__ __launch_bounds__(256) void warmup_mix_kernel(const T* __restrict__ s
 #pragma unroll
     for (int i = 0; i < N; ++i) acc[i] = fmaf(scale, acc[i], f0[i]);
     q.pack(acc);
-    q.store(dst + (long)j * elems + v * N);
+    q.store_once(dst + (long)j * elems + v * N);
   }
 }
 

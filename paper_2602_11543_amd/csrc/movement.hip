@@ -17,10 +17,10 @@ __global__ __launch_bounds__(256) void permute_kernel(const T* __restrict__ x, c
     const long t = v / nvec;
     const int c = (int)(v - t * nvec);
     Vec16<T> q;
-    q.load(x + t * d + c * N);
+    q.load_once(x + t * d + c * N);
     for (int j = 0; j < k; ++j) {
       const long r = inv[t * k + j];
-      q.store(xp + r * d + c * N);
+      q.store_once(xp + r * d + c * N);
     }
   }
 }
@@ -45,7 +45,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ yp, 
       for (int j = 0; j < KU; ++j) {
         const long r = inv[t * KU + j];
         g[j] = gate[t * KU + j];
-        q[j].load(yp + r * d + c * N);
+        q[j].load_once(yp + r * d + c * N);
       }
 #pragma unroll
       for (int j = 0; j < KU; ++j) {
@@ -59,7 +59,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ yp, 
         const long r = inv[t * k + j];
         const float g = gate[t * k + j];
         Vec16<T> q;
-        q.load(yp + r * d + c * N);
+        q.load_once(yp + r * d + c * N);
         float f[N];
         q.unpack(f);
 #pragma unroll
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ yp, 
     }
     Vec16<T> o;
     o.pack(acc);
-    o.store(y + t * d + c * N);
+    o.store_once(y + t * d + c * N);
   }
 }
 
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void dx_gather_kernel(const T* __restrict__ dx
     for (int i = 0; i < N; ++i) acc[i] = 0.f;
     for (int j = 0; j < k; ++j) {
       Vec16<T> q;
-      q.load(dxp + (long)rows[j] * d + c * N);
+      q.load_once(dxp + (long)rows[j] * d + c * N);
       float f[N];
       q.unpack(f);
 #pragma unroll
@@ -100,7 +100,7 @@ __global__ __launch_bounds__(256) void dx_gather_kernel(const T* __restrict__ dx
     }
     if (dxr != nullptr) {
       Vec16<T> q;
-      q.load(dxr + t * d + c * N);
+      q.load_once(dxr + t * d + c * N);
       float f[N];
       q.unpack(f);
 #pragma unroll
@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256) void dx_gather_kernel(const T* __restrict__ dx
     }
     Vec16<T> o;
     o.pack(acc);
-    o.store(dx + t * d + c * N);
+    o.store_once(dx + t * d + c * N);
   }
 }
 

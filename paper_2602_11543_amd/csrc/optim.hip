@@ -31,10 +31,10 @@ __global__ __launch_bounds__(256) void masked_adamw_kernel(const SlotTable tb, T
   float* w = master ? master + so : reinterpret_cast<float*>(p);
   const long stride = (long)gridDim.x * 256;
   for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < nvec; i += stride) {
-    const float4 g4 = *reinterpret_cast<const float4*>(grad + so + i * 4);
-    const float4 m4 = *reinterpret_cast<const float4*>(m + so + i * 4);
-    const float4 v4 = *reinterpret_cast<const float4*>(v + so + i * 4);
-    const float4 w4 = *reinterpret_cast<const float4*>(w + i * 4);
+    const float4 g4 = load_stream(reinterpret_cast<const float4*>(grad + so + i * 4));
+    const float4 m4 = load_stream(reinterpret_cast<const float4*>(m + so + i * 4));
+    const float4 v4 = load_stream(reinterpret_cast<const float4*>(v + so + i * 4));
+    const float4 w4 = load_stream(reinterpret_cast<const float4*>(w + i * 4));
     const float g[4] = {g4.x, g4.y, g4.z, g4.w};
     float mm[4] = {m4.x, m4.y, m4.z, m4.w}, vv[4] = {v4.x, v4.y, v4.z, v4.w}, ww[4] = {w4.x, w4.y, w4.z, w4.w};
 #pragma unroll
@@ -45,9 +45,9 @@ __global__ __launch_bounds__(256) void masked_adamw_kernel(const SlotTable tb, T
       const float upd = (mm[e] * h.inv_bc1) / (sqrtf(vv[e] * h.inv_bc2) + h.eps) + h.wd * ww[e];
       ww[e] -= h.lr * upd;
     }
-    *reinterpret_cast<float4*>(m + so + i * 4) = make_float4(mm[0], mm[1], mm[2], mm[3]);
-    *reinterpret_cast<float4*>(v + so + i * 4) = make_float4(vv[0], vv[1], vv[2], vv[3]);
-    *reinterpret_cast<float4*>(w + i * 4) = make_float4(ww[0], ww[1], ww[2], ww[3]);
+    store_stream(reinterpret_cast<float4*>(m + so + i * 4), make_float4(mm[0], mm[1], mm[2], mm[3]));
+    store_stream(reinterpret_cast<float4*>(v + so + i * 4), make_float4(vv[0], vv[1], vv[2], vv[3]));
+    store_stream(reinterpret_cast<float4*>(w + i * 4), make_float4(ww[0], ww[1], ww[2], ww[3]));
     if (master) {
       if (sizeof(T) == 2) {
         *reinterpret_cast<uint2*>(p + i * 4) = make_uint2(pack_bf16x2(ww[0], ww[1]), pack_bf16x2(ww[2], ww[3]));

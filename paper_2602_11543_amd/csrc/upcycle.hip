@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256) void upcycle_kernel(const T* __restrict__ dens
       for (int j = 0; j < 4; ++j) f[4 * h + j] += nz[j];
     }
     q.pack(f);
-    q.store(out + (long)e * elems + v * N);
+    q.store_once(out + (long)e * elems + v * N);
   }
 }
 
@@ -79,7 +79,7 @@ __global__ __launch_bounds__(256) void pack_kernel(const PackTable tb, uint4* __
   uint4* comp = packed + (slot0 + s) * vec_per_row;
   const long stride = (long)gridDim.x * 256;
   for (long v = (long)blockIdx.x * 256 + threadIdx.x; v < nvec; v += stride) {
-    if (to_store) full[v] = comp[v]; else comp[v] = full[v];
+    if (to_store) store_stream(full + v, load_stream(comp + v)); else store_stream(comp + v, load_stream(full + v));
   }
 }
 
