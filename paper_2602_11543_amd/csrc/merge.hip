@@ -36,7 +36,22 @@ __global__ __launch_bounds__(256) void sync_merge_kernel(const MergeTable tb, T*
       q.unpack(f0);
 #pragma unroll
       for (int i = 0; i < N; ++i) acc[i] = f0[i];
-      for (int s = 1; s < n; ++s) {
+      // four copies are requested before the first is used; the order of the additions stays s = 1, 2, ...
+      int s = 1;
+      for (; s + 4 <= n; s += 4) {
+        Vec16<T> qs[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) qs[u].load_once(reinterpret_cast<const T*>(tb.src[b + s + u]) + v * N);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          float f[N];
+          qs[u].unpack(f);
+          const float w = tb.w[b + s + u];
+#pragma unroll
+          for (int i = 0; i < N; ++i) acc[i] = fmaf(w, f[i] - f0[i], acc[i]);
+        }
+      }
+      for (; s < n; ++s) {
         Vec16<T> qs;
         qs.load_once(reinterpret_cast<const T*>(tb.src[b + s]) + v * N);
         float f[N];
@@ -106,7 +121,7 @@ __global__ __launch_bounds__(256) void warmup_mix_kernel(const T* __restrict__ s
   const long stride = (long)gridDim.x * 256;
   for (long v = (long)blockIdx.x * 256 + threadIdx.x; v < nvec; v += stride) {
     Vec16<T> q;
-    q.load(src + (long)j * elems + v * N);
+    q.load(src + (long)j * elems + v * N);      // rows are read again as peers of other experts: no streaming hint
     float f0[N], acc[N];
     q.unpack(f0);
 #pragma unroll
