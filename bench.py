@@ -2,9 +2,11 @@
 """Benchmark of the SPES MoE-layer hot path on one MI355X.
 
 One step = one forward plus one backward of the routed SwiGLU layer (every stage
-of the hot path: router GEMM, softmax/top-k, histogram/scan/rank, permute, grouped
+of the hot path: router GEMM, softmax/top-k, histogram/scan/rank, dispatch, grouped
 expert GEMMs, combine; backward with weight gradients for the trainable experts
-only) over one batch of seeded synthetic tokens already resident in HBM.
+only) over one batch of seeded synthetic tokens already resident in HBM.  The
+dispatch copy is fused into the operand reads of the grouped GEMMs; its stand-alone
+kernel (spes_moe_permute) is timed beside the step and reported with in_step false.
 
 Prints one JSON line: layer tokens/s, the roofline position of the dominant kernel
 (measured with HIP events recorded between stages on the launch stream), per-stage
@@ -86,7 +88,9 @@ def stage_model(cfg, rho_rows):
         "wgrad_gate": (mm, 2.0 * rho_rows * d * f),
         "wgrad_up": (mm, 2.0 * rho_rows * d * f),
         "router_wgrad": ("hbm", T * d * s + T * M * 4 + M * d * 4),
-        "unpermute_sum_router_dgrad": ("hbm", R * d * s + T * d * s + R * 4),
+        "router_dgrad": ("hbm", T * M * 2 + M * d * s + T * d * s),          # bf16 storage only: its own small GEMM
+        # sum of the k permuted gradient rows plus the router part (read as a precomputed row in bf16 storage)
+        "unpermute_sum_router_dgrad": ("hbm", R * d * s + T * d * s + R * 4 + (T * d * s if s == 2 else 0)),
     }
 
 
@@ -365,12 +369,24 @@ def main() -> int:
             acc[n] = acc.get(n, 0.0) + ms
     S.spes_profile_enable(False)
     stage_ms = {n: v / args.steps for n, v in acc.items()}
+    # the dispatch copy is not part of the step (the grouped GEMMs read x through the routing table); its stand-alone
+    # kernel is timed here on the same stream, from the routing tables the last forward left in ctx
+    xp = torch.empty(cfg.T * cfg.k, cfg.d, dtype=L.x.dtype, device=dev)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    S.spes_moe_permute(L.shape, L.x, L.ctx, xp)
+    ev[0].record()
+    for _ in range(args.steps):
+        S.spes_moe_permute(L.shape, L.x, L.ctx, xp)
+    ev[1].record()
+    torch.cuda.synchronize()
+    standalone = {"permute": ev[0].elapsed_time(ev[1]) / args.steps}
+    del xp
 
     count = L.count.cpu().numpy()
     rows_trainable = int(count[np.nonzero(L.mask)[0]].sum())
     model = stage_model(cfg, rows_trainable)
     stages = {}
-    for n, ms in stage_ms.items():
+    for n, ms in list(stage_ms.items()) + list(standalone.items()):
         bound, amount = model[n]
         if bound == "hbm":
             ach, peak, unit = amount / (ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
@@ -378,6 +394,8 @@ def main() -> int:
             ach, unit = amount / (ms * 1e-3) / 1e12, "TFLOP/s"
             peak = PEAK_BF16_TFLOPS if bound == "mfma" else PEAK_FP32_TFLOPS
         stages[n] = dict(ms=round(ms, 4), bound=bound, achieved=round(ach, 2), peak=peak, unit=unit, frac=round(ach / peak, 4))
+        if n in standalone:
+            stages[n]["in_step"] = False       # timed on its own: the step does not run it
     dominant = max(stage_ms, key=stage_ms.get)
     dom = stages[dominant]
     gemm_names = [n for n, (b, _) in model.items() if b in ("mfma", "alu") and n in stage_ms]

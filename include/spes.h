@@ -72,7 +72,6 @@ typedef struct {
   size_t offset;    /* [M+1] i32 first row of each expert in expert-contiguous order  */
   size_t perm;      /* [R] i32 row r holds routed pair perm[r] = t*k+j                */
   size_t inv;       /* [R] i32 inverse of perm                                        */
-  size_t xp;        /* [R,d] permuted inputs                                          */
   size_t a;         /* [R,f] f32 gate projection  W_g x (fp32: the gate gradient needs it) */
   size_t b;         /* [R,f] f32 up projection    W_u x                                */
   size_t h;         /* [R,f] SiLU(a)*b                                                */
@@ -105,6 +104,19 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
                           const float* router_bias, const void* w_gate, const void* w_up,
                           const void* w_down, void* y, int32_t* topk_idx, float* topk_gate,
                           int32_t* expert_count, void* ctx, void* stream);
+
+/* The permuted copy of the input that drop-less dispatch defines (Sec. 3.2): row r of xp is
+ * the input row of the routed pair that the forward placed at position r of the
+ * expert-contiguous order, xp[inv[t*k+j], :] = x[t, :].  spes_moe_fwd and spes_moe_bwd do not
+ * need it (their grouped GEMMs read x through the same table); this entry point materialises
+ * it for callers that want the dispatched activations, and is the stand-alone form of the
+ * dispatch step.
+ *
+ *  x    DEVICE [T,d]       ctx  DEVICE, as left by spes_moe_fwd for this shape
+ *  xp   DEVICE [T*k,d] out, must not alias x
+ */
+SPES_API int spes_moe_permute(const spes_moe_shape* shape, const void* x, const void* ctx, void* xp,
+                              void* stream);
 
 /* Backward of the same layer for upstream gradient dy.  The selected expert set
  * is treated as constant.  The input gradient flows through every routed expert,

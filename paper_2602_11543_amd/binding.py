@@ -27,7 +27,7 @@ class spes_moe_shape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("T", "d_model", "n_experts", "d_ff", "top_k", "dtype", "renorm_topk")]
 
 
-_LAYOUT_FIELDS = ("total", "logits", "lse", "topk_idx", "topk_gate", "offset", "perm", "inv", "xp", "a", "b", "h", "yp",
+_LAYOUT_FIELDS = ("total", "logits", "lse", "topk_idx", "topk_gate", "offset", "perm", "inv", "a", "b", "h", "yp",
                   "dlogits", "dgate")
 
 
@@ -49,6 +49,8 @@ def _load() -> ctypes.CDLL:
     lib.spes_moe_fwd.argtypes = [shp] + [vp] * 12
     lib.spes_moe_bwd.restype = i32
     lib.spes_moe_bwd.argtypes = [shp] + [vp] * 13 + [i32, vp]
+    lib.spes_moe_permute.restype = i32
+    lib.spes_moe_permute.argtypes = [shp, vp, vp, vp, vp]
     lib.spes_moe_router_aux.restype = i32
     lib.spes_moe_router_aux.argtypes = [shp, vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, vp, vp]
     lib.spes_masked_adamw.restype = i32
@@ -137,6 +139,10 @@ def spes_moe_bwd(shape, dy, x, w_router, w_gate, w_up, w_down, ctx, trainable_ma
                              _dev(d_w_up), _dev(d_w_down), int(accumulate), _stream(stream)), "spes_moe_bwd")
 
 
+def spes_moe_permute(shape, x, ctx, xp, stream=None) -> None:
+    _check(_lib.spes_moe_permute(ctypes.byref(shape), _dev(x), _dev(ctx), _dev(xp), _stream(stream)), "spes_moe_permute")
+
+
 def spes_moe_router_aux(shape, ctx, lb_coef, z_coef, grad_scale, losses, stream=None) -> None:
     _check(_lib.spes_moe_router_aux(ctypes.byref(shape), _dev(ctx), float(lb_coef), float(z_coef), float(grad_scale),
                                     _dev(losses), _stream(stream)), "spes_moe_router_aux")
@@ -218,7 +224,7 @@ def ctx_view(shape: spes_moe_shape, ctx: torch.Tensor, name: str) -> torch.Tenso
     st = torch_dtype(shape.dtype)
     spec = dict(logits=(torch.float32, (T, M)), lse=(torch.float32, (T,)), topk_idx=(torch.int32, (T, k)),
                 topk_gate=(torch.float32, (T, k)), offset=(torch.int32, (M + 1,)), perm=(torch.int32, (R,)),
-                inv=(torch.int32, (R,)), xp=(st, (R, d)), a=(torch.float32, (R, f)), b=(torch.float32, (R, f)), h=(st, (R, f)), yp=(st, (R, d)),
+                inv=(torch.int32, (R,)), a=(torch.float32, (R, f)), b=(torch.float32, (R, f)), h=(st, (R, f)), yp=(st, (R, d)),
                 dlogits=(torch.float32, (T, M)), dgate=(torch.float32, (T, k)))[name]
     n = int(np.prod(spec[1])) * torch.empty((), dtype=spec[0]).element_size()
     return ctx[lay[name]: lay[name] + n].view(spec[0]).view(spec[1])

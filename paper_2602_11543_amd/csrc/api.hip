@@ -55,7 +55,6 @@ Layout make_layout(const spes_moe_shape* s) {
   L.tab_mfma = take((1 + 2 * (size_t)L.max_tiles) * 4);
   L.row_token = take(R * 4);
   L.row_gate = take(R * 4);
-  L.pub.xp = take(R * d * es);
   L.pub.a = take(R * f * 4);
   L.pub.b = take(R * f * 4);
   L.pub.h = take(R * f * es);
@@ -187,12 +186,11 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
                                  at<int>(ctx, L.tab_simt), mfma_row_tile(), at<int>(ctx, L.tab_mfma), L.max_tiles,
                                  at<float>(ctx, L.aux), s));
   prof_mark(0, "hist_scan_rank", s);
-  SPES_TRY(launch_permute(dt, x, at<int>(ctx, L.pub.inv), k, at<void>(ctx, L.pub.xp), T, d, s));
-  prof_mark(0, "permute", s);
-  // a = xp W_g^T, b = xp W_u^T, h = SiLU(a) * b
+  // a = xp W_g^T, b = xp W_u^T, h = SiLU(a) * b with xp[r,:] = x[token of row r,:]: the GEMM reads its operand rows
+  // through the row -> token table, the permuted copy of x is never written (spes_moe_permute materialises it)
   {
     GemmArgs g = blank();
-    g.A[0] = at<void>(ctx, L.pub.xp); g.a_ms = d; g.a_ks = 1; g.a_elems = R * d;
+    g.A[0] = x; g.a_ms = d; g.a_ks = 1; g.a_elems = (long)T * d; g.a_rows = at<int>(ctx, L.row_token);
     g.B[0] = w_gate; g.B[1] = w_up; g.b_ns = d; g.b_ks = 1; g.b_gs = (long)f * d; g.b_elems = (long)M * f * d;
     g.Kdim = d; g.Ndim = f;
     g.C[0] = at<void>(ctx, L.pub.a); g.C[1] = at<void>(ctx, L.pub.b); g.C[2] = at<void>(ctx, L.pub.h); g.c_ms = f;
@@ -214,6 +212,15 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
   SPES_TRY(launch_combine(dt, at<void>(ctx, L.pub.yp), at<int>(ctx, L.pub.inv), topk_gate, y, T, d, k, s));
   prof_mark(0, "combine", s);
   return SPES_OK;
+}
+
+SPES_API int spes_moe_permute(const spes_moe_shape* shape, const void* x, const void* ctx, void* xp, void* stream) {
+  SPES_TRY(shape_supported(shape));
+  if (!x || !ctx || !xp) return SPES_EINVAL;
+  if (!aligned16(x) || !aligned16(ctx) || !aligned16(xp)) return SPES_EALIGN;
+  const Layout L = make_layout(shape);
+  return launch_permute(shape->dtype, x, at<int>(const_cast<void*>(ctx), L.pub.inv), shape->top_k, xp, shape->T, shape->d_model,
+                        static_cast<hipStream_t>(stream));
 }
 
 SPES_API int spes_moe_router_aux(const spes_moe_shape* shape, void* ctx, float lb_coef, float z_coef, float grad_scale,
@@ -303,7 +310,7 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
     SPES_TRY(expert_gemm(dt, kGroupedK, kEpiStore, false, false, g, s));
     prof_mark(1, "wgrad_down", s);
     // dW_g[f,d] = da^T xp ; dW_u[f,d] = db^T xp
-    g.B[0] = at<void>(ctx, L.pub.xp); g.b_ns = 1; g.b_ks = d; g.b_elems = R * d;
+    g.B[0] = x; g.b_rows = at<int>(ctx, L.row_token); g.b_ns = 1; g.b_ks = d; g.b_elems = (long)T * d;
     g.a_ms = 1; g.a_ks = f; g.a_rows = nullptr; g.a_elems = R * f; g.Mdim = f; g.Ndim = d; g.c_ms = d; g.c_gs = (long)f * d;
     g.A[0] = at<void>(ctx, L.da); g.C[0] = d_w_gate;
     SPES_TRY(expert_gemm(dt, kGroupedK, kEpiStore, false, false, g, s));
@@ -339,6 +346,7 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
     g.Kdim = M; g.kchunk = (M + 63) / 64 * 64; g.Mdim = T; g.Ndim = d;
     g.C[0] = at<void>(ctx, L.dxr); g.c_ms = d;
     SPES_TRY(launch_gemm_mfma(kGroupedK, kEpiStore, true, false, g, s));
+    prof_mark(1, "router_dgrad", s);
   }
   // dx = unpermuted sum of dxp + router part
   SPES_TRY(launch_dx_gather(dt, at<void>(ctx, L.dxp), inv, at<float>(ctx, L.pub.dlogits), w_router,

@@ -29,6 +29,7 @@ struct GemmArgs {
   long a_elems, b_elems;  // matrix-core path: elements addressable from A[i] and from B[i] (reads beyond return zero)
   long a_ms, a_ks;        // element strides of A along m, k
   const int* a_rows;      // optional gather: kRaggedM reads row a_rows[m] in place of m; kGroupedK reads row a_rows[k] in place of k
+  const int* b_rows;      // optional gather, kGroupedK with K-strided B only: B reads row b_rows[k] in place of k
   const float* row_scale; // kEpiDSwiglu: per-row factor (the gate of the routed pair)
   float* rowdot;          // kEpiDSwiglu: [gridDim.x, rowdot_stride] partial gate gradients
   long rowdot_stride;

@@ -97,8 +97,9 @@ __device__ __forceinline__ uint2 lds_read_tr(const bf16_t* p) {
   return __builtin_bit_cast(uint2, v);
 }
 
-// A_KG: the K-strided operand A takes its k-rows through the index table a_rows (dy rows of an expert)
-template <int MODE, int EPI, bool A_KC, bool B_KC, bool A_KG, typename C>
+// A_KG / B_KG: the K-strided operand A / B takes its k-rows through the index table a_rows / b_rows (the dy rows,
+// or the input rows, of an expert's routed pairs)
+template <int MODE, int EPI, bool A_KC, bool B_KC, bool A_KG, bool B_KG, typename C>
 __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs g) {
   constexpr int BM = C::BM, BN = C::BN, BK = C::BK, TM = C::TM, TN = C::TN, CH = C::CH, RP = C::RP;
   __shared__ uint4 smem[2 * C::STAGE_VEC];
@@ -226,12 +227,21 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   // gathered k-rows of the tile about to be loaded; fetched one tile ahead so that no load waits on an index
   constexpr int ACH = BM / 8, BCH = BN / 8;     // 16-byte chunks per k-row of a K-strided tile
   int kidx[A_KG ? C::NAS : 1];
+  int kidx_b[B_KG ? C::NBS : 1];
   auto load_kidx = [&](int step) {
     if (A_KG) {
       const int st = step < nsteps ? step : nsteps - 1;
       const long k = k_begin + (long)(st % nk) * BK + tid / ACH;
 #pragma unroll
       for (int j = 0; j < C::NAS; ++j) kidx[j] = g.a_rows[k + j * C::KRA < k_end ? k + j * C::KRA : k_end - 1];
+    }
+  };
+  auto load_kidx_b = [&](int step) {
+    if (B_KG) {
+      const int st = step < nsteps ? step : nsteps - 1;
+      const long k = k_begin + (long)(st % nk) * BK + tid / BCH;
+#pragma unroll
+      for (int j = 0; j < C::NBS; ++j) kidx_b[j] = g.b_rows[k + j * C::KRB < k_end ? k + j * C::KRB : k_end - 1];
     }
   };
   // registers 0..n-1 of a K-strided operand hold k-rows inside the contraction range
@@ -274,6 +284,10 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
       // (the register -> matrix assignment of the fused SwiGLU is the same for every thread)
       const bool second = (EPI == kEpiSwiglu) ? (((RP * idx) % SW_W) / SW_H) != 0 : l_pass != 0;
       rb[idx] = buffer_load16(second ? b_rsrc[1] : b_rsrc[0], boff[idx], (unsigned)((k_begin + l_kq) * 2));
+    } else if (B_KG) {
+      rb[idx] = buffer_load16(l_pass ? b_rsrc[1] : b_rsrc[0],
+                              (unsigned)kidx_b[idx] * (unsigned)(g.b_ks * 2) + (unsigned)((n0 + (tid % BCH) * 8) * 2), 0u);
+      if (idx == C::NBS - 1) load_kidx_b(l_step + 1);
     } else {
       rb[idx] = buffer_load16(l_pass ? b_rsrc[1] : b_rsrc[0], b_ks_off, (unsigned)((k_begin + l_kq + idx * C::KRB) * g.b_ks * 2));
     }
@@ -345,6 +359,7 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   if (nsteps > 0) {
     // prologue: tile 0 -> registers -> LDS stage 0, tile 1 -> registers
     load_kidx(0);
+    load_kidx_b(0);
     set_load_tile(0);
 #pragma unroll
     for (int p = 0; p < NP; ++p) piece(p, 0, false, true, true);
@@ -599,10 +614,13 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
 // one tile configuration: 256 x 256 x 64, one block per CU (144 KB of LDS, 256 accumulators per lane in AGPRs)
 typedef Cfg<256, 256, 64, 1> Tile;
 
-template <int MODE, int EPI, bool A_KC, bool B_KC, bool A_KG = false>
+template <int MODE, int EPI, bool A_KC, bool B_KC, bool A_KG = false, bool B_KG = false>
 int launch(const GemmArgs& g, hipStream_t s) {
   typedef Tile C;
   static_assert(!A_KG || !A_KC, "k-row gather: K-strided A only");
+  static_assert(!B_KG || (!B_KC && MODE == kGroupedK), "k-row gather of B: K-strided B of a grouped contraction only");
+  static_assert(!(A_KG && B_KG), "one gathered operand per launch");
+  if (B_KG && g.npairs != 1) return SPES_EINVAL;
   // operands are addressed with 32-bit byte offsets from their base
   if (g.a_elems <= 0 || g.b_elems <= 0) return SPES_EINVAL;
   if (g.a_elems >= (1L << 31) || g.b_elems >= (1L << 31)) return SPES_ESHAPE;
@@ -611,7 +629,7 @@ int launch(const GemmArgs& g, hipStream_t s) {
   long total = (MODE == kRaggedM) ? (long)g.max_tiles * gx : (long)g.n_groups * cdiv(g.Mdim, C::BM) * gx;
   if (total <= 0) return SPES_OK;
   total = (total + kXcds - 1) / kXcds * kXcds;
-  hipLaunchKernelGGL((gemm_mfma_kernel<MODE, EPI, A_KC, B_KC, A_KG, C>), dim3((unsigned)total), dim3(256), 0, s, g);
+  hipLaunchKernelGGL((gemm_mfma_kernel<MODE, EPI, A_KC, B_KC, A_KG, B_KG, C>), dim3((unsigned)total), dim3(256), 0, s, g);
   return hipGetLastError() == hipSuccess ? SPES_OK : SPES_EHIP;
 }
 
@@ -624,7 +642,7 @@ int mfma_rowdot_parts(int ndim) { return 2 * cdiv(ndim, Tile::BN); }
 // bf16 operands only.  a_kcontig / b_kcontig: the contraction index is the fast memory axis of that operand.
 int launch_gemm_mfma(int mode, int epi, bool a_kcontig, bool b_kcontig, const GemmArgs& g, hipStream_t s) {
   if (mode == kRaggedM) {
-    if (!a_kcontig) return SPES_EINVAL;
+    if (!a_kcontig || g.b_rows) return SPES_EINVAL;
     if (epi == kEpiSwiglu && b_kcontig) return launch<kRaggedM, kEpiSwiglu, true, true>(g, s);
     if (epi == kEpiStore && b_kcontig) return launch<kRaggedM, kEpiStore, true, true>(g, s);
     if (epi == kEpiStore && !b_kcontig) return launch<kRaggedM, kEpiStore, true, false>(g, s);
@@ -634,8 +652,12 @@ int launch_gemm_mfma(int mode, int epi, bool a_kcontig, bool b_kcontig, const Ge
   if (epi != kEpiStore) return SPES_EINVAL;
   if (a_kcontig && b_kcontig) return launch<kGroupedK, kEpiStore, true, true>(g, s);
   if (a_kcontig && !b_kcontig) return launch<kGroupedK, kEpiStore, true, false>(g, s);
-  if (!a_kcontig && !b_kcontig)
-    return g.a_rows ? launch<kGroupedK, kEpiStore, false, false, true>(g, s) : launch<kGroupedK, kEpiStore, false, false>(g, s);
+  if (g.b_rows && (a_kcontig || b_kcontig || g.a_rows)) return SPES_EINVAL;
+  if (!a_kcontig && !b_kcontig) {
+    if (g.a_rows) return launch<kGroupedK, kEpiStore, false, false, true>(g, s);
+    if (g.b_rows) return launch<kGroupedK, kEpiStore, false, false, false, true>(g, s);
+    return launch<kGroupedK, kEpiStore, false, false>(g, s);
+  }
   return SPES_EINVAL;
 }
 

@@ -90,7 +90,12 @@ __global__ __launch_bounds__(256) void gemm_simt_kernel(const GemmArgs g) {
           int nl, kl;
           if (b_kfast) { nl = tid >> 2; kl = (tid & 3) * 4 + i; } else { kl = tid >> 4; nl = (tid & 15) * 4 + i; }
           const long n = n0 + nl, k = kk + kl;
-          Bs[p][kl][nl] = (n < g.Ndim && k < k_end) ? ld<TB>(Bp, b_group + n * g.b_ns + k * g.b_ks) : 0.f;
+          float v = 0.f;
+          if (n < g.Ndim && k < k_end) {
+            const long row = (MODE == kGroupedK && g.b_rows) ? (long)g.b_rows[k] : k;
+            v = ld<TB>(Bp, b_group + n * g.b_ns + row * g.b_ks);
+          }
+          Bs[p][kl][nl] = v;
         }
       }
       __syncthreads();

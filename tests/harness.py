@@ -71,6 +71,12 @@ class DeviceLayer:
         S.spes_moe_router_aux(self.shape, self.ctx, lb_coef, z_coef, grad_scale, losses)
         return tuple(float(v) for v in losses.cpu().numpy())
 
+    def permuted(self):
+        """The dispatched copy of x in expert-contiguous order, from the routing tables of the last forward."""
+        xp = torch.empty(self.cfg.T * self.cfg.k, self.cfg.d, dtype=self.x.dtype, device=self.dev)
+        S.spes_moe_permute(self.shape, self.x, self.ctx, xp)
+        return xp
+
     def view(self, name):
         return S.ctx_view(self.shape, self.ctx, name)
 
@@ -94,3 +100,7 @@ def check_routing(L: DeviceLayer, fwd) -> None:
     assert np.array_equal(L.view("perm").cpu().numpy(), fwd["perm"]), "permutation differs"
     assert np.array_equal(L.view("inv").cpu().numpy(), fwd["inv"])
     assert int(L.count.sum()) == cfg.T * cfg.k
+    # dispatch is a copy: row r of the permuted input is the input row of pair perm[r], bit for bit
+    xp = L.permuted()
+    want = L.x[torch.from_numpy(fwd["perm"] // cfg.k).to(L.dev).long()]
+    assert torch.equal(xp.view(torch.uint8), want.contiguous().view(torch.uint8)), "permuted input differs"

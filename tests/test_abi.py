@@ -64,6 +64,11 @@ def test_argument_checks_run_before_any_launch():
     mask = (ctypes.c_uint8 * 8)(1, 0, 0, 0, 0, 0, 0, 0)
     bwd_args = [p[0], p[1], p[2], p[3], p[4], p[5], p[6], ctypes.cast(mask, ctypes.c_void_p), p[7], p[8], None, p[9], p[10]]
     assert lib.spes_moe_bwd(ctypes.byref(ok_shape), *bwd_args, 0, None) == -1   # a trainable expert but no d_w_gate buffer
+    lib.spes_moe_permute.restype = ctypes.c_int32
+    lib.spes_moe_permute.argtypes = [ctypes.c_void_p] * 5
+    assert lib.spes_moe_permute(ctypes.byref(ok_shape), p[0], p[1], None, None) == -1                   # no output
+    assert lib.spes_moe_permute(ctypes.byref(ok_shape), p[0], p[1], _fake(0x20004), None) == -3         # misaligned output
+    assert lib.spes_moe_permute(ctypes.byref(S.moe_shape(64, 60, 8, 64, 2, 1, 0)), p[0], p[1], p[2], None) == -2
     lib.spes_moe_router_aux.restype = ctypes.c_int32
     lib.spes_moe_router_aux.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_float, ctypes.c_float,
                                         ctypes.c_void_p, ctypes.c_void_p]

@@ -39,6 +39,12 @@ def _check_sampled(L, inp, rt, n_tokens=768, n_experts=2, seed=0):
     assert np.array_equal(L.view("perm").cpu().numpy(), rt["perm"])
     assert np.array_equal(L.view("inv").cpu().numpy(), rt["inv"])
     assert rel_err(L.gate.cpu().numpy(), rt["gate"]) <= 1e-5
+    # the dispatched copy of x, every row: a byte-exact gather through the (oracle-checked) permutation
+    xp = L.permuted()
+    tok = torch.from_numpy(rt["perm"] // cfg.k).to(L.dev).long()
+    for r0 in range(0, tok.numel(), 1 << 16):
+        assert torch.equal(xp[r0:r0 + (1 << 16)].view(torch.uint8), L.x[tok[r0:r0 + (1 << 16)]].view(torch.uint8)), "permuted input differs"
+    del xp
     # ---- sampled tokens: y, dx, dgate, dlogits ----
     pick = np.sort(rng.choice(cfg.T, size=min(n_tokens, cfg.T), replace=False))
     fwd = O.moe_forward(inp["x"][pick], inp["w_router"], inp["router_bias"], inp["w_gate"], inp["w_up"], inp["w_down"],
