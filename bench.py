@@ -382,6 +382,21 @@ def main() -> int:
     standalone = {"permute": ev[0].elapsed_time(ev[1]) / args.steps}
     del xp
 
+    # what the matrix cores reach on this device with operand values like the workload's (the shader clock under
+    # matrix load is power-limited and depends on the data): a register-resident MFMA loop, no memory traffic at all;
+    # run after everything that is timed, so that it does not eat into their power budget
+    mfma_tflops = None
+    if cfg.dtype == "bf16":
+        sink = torch.empty(256, dtype=torch.float32, device=dev)
+        S.spes_ref_mfma_rate(L.w_gate, 256, 4000, sink)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flop = sum(S.spes_ref_mfma_rate(L.w_gate, 256, 20000, sink) for _ in range(3))
+        e1.record()
+        torch.cuda.synchronize()
+        mfma_tflops = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
     count = L.count.cpu().numpy()
     rows_trainable = int(count[np.nonzero(L.mask)[0]].sum())
     model = stage_model(cfg, rows_trainable)
@@ -421,6 +436,11 @@ def main() -> int:
                                "what": "plain 1 GiB device-to-device copy (read + write bytes) on this GPU"},
         "stages": stages,
     }
+    if mfma_tflops is not None:
+        out["mfma_reference"] = {"achieved": round(mfma_tflops, 1), "unit": "TFLOP/s", "frac_of_nominal": round(mfma_tflops / PEAK_BF16_TFLOPS, 4),
+                                 "what": "register-resident 32x32x16 bf16 MFMA loop on this GPU, operands taken from the workload's expert "
+                                         "weights: the power-limited matrix rate on data like the workload's"}
+        out["grouped_gemm_util"]["frac_of_mfma_reference"] = round(gemm_flop / (gemm_ms * 1e-3) / 1e12 / mfma_tflops, 4)
     tr = profiled_traffic(cfg.name, dominant)
     if tr is not None:
         out["roofline"]["traffic"] = tr["bytes"]           # HBM-side bytes per launch (offline counters, see traffic_detail)

@@ -256,6 +256,19 @@ SPES_API int spes_expert_warmup_merge(int32_t n_experts, int32_t dtype, int32_t 
                                       const int64_t* elems, float* sim, int32_t* nbr,
                                       void* scratch, void* stream);
 
+/* Reference rate of the matrix cores, for benchmarks: launches `blocks` workgroups of four
+ * wavefronts that each run `iters` rounds of sixteen 32x32x16 bf16 MFMAs on operands held in
+ * registers, taken from `data`.  The shader clock under matrix load depends on the operand
+ * values (power), so the rate to compare a GEMM with is this loop timed on values like the
+ * GEMM's.  The caller times the launch (events on `stream`); *flop receives the number of
+ * floating-point operations it performs.
+ *
+ *  data   DEVICE, 64 KiB of bf16 operand values     sink  DEVICE [blocks] f32 out (no meaning)
+ *  flop   HOST out, may be NULL
+ */
+SPES_API int spes_ref_mfma_rate(const void* data, int32_t blocks, int32_t iters, float* sink,
+                                double* flop, void* stream);
+
 /* Stage timing for benchmarks.  While enabled, spes_moe_fwd / spes_moe_bwd record a
  * HIP event on the caller's stream after each of their stages (the steps of the hot
  * path: router GEMM, softmax/top-k, histogram/scan/rank, permute, the grouped GEMMs,

@@ -65,6 +65,8 @@ def _load() -> ctypes.CDLL:
     lib.spes_warmup_scratch_bytes.argtypes = [i32, i64]
     lib.spes_expert_warmup_merge.restype = i32
     lib.spes_expert_warmup_merge.argtypes = [i32, i32, i32, ctypes.c_float, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.spes_ref_mfma_rate.restype = i32
+    lib.spes_ref_mfma_rate.argtypes = [vp, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.spes_profile_enable.restype = i32
     lib.spes_profile_enable.argtypes = [i32]
     lib.spes_profile_read.restype = i32
@@ -214,6 +216,14 @@ def spes_profile_read(which: int) -> list:
     if n < 0:
         _check(n, "spes_profile_read")
     return [(names[i].decode(), float(ms[i])) for i in range(n)]
+
+
+def spes_ref_mfma_rate(data, blocks, iters, sink, stream=None) -> float:
+    """Launches the register-resident MFMA loop; returns the floating-point operations it performs."""
+    flop = ctypes.c_double(0.0)
+    _check(_lib.spes_ref_mfma_rate(_dev(data), int(blocks), int(iters), _dev(sink), ctypes.byref(flop), _stream(stream)),
+           "spes_ref_mfma_rate")
+    return float(flop.value)
 
 
 def ctx_view(shape: spes_moe_shape, ctx: torch.Tensor, name: str) -> torch.Tensor:

@@ -463,6 +463,12 @@ SPES_API int spes_expert_warmup_merge(int32_t n_experts, int32_t dtype, int32_t 
   return SPES_OK;
 }
 
+SPES_API int spes_ref_mfma_rate(const void* data, int32_t blocks, int32_t iters, float* sink, double* flop, void* stream) {
+  if (!data || !sink || blocks <= 0 || iters <= 0 || blocks > (1 << 20)) return SPES_EINVAL;
+  if (!aligned16(data) || !aligned16(sink)) return SPES_EALIGN;
+  return launch_mfma_rate(data, blocks, iters, sink, flop, static_cast<hipStream_t>(stream));
+}
+
 SPES_API int spes_profile_enable(int32_t on) {
   if (on && !g_prof.created) {
     for (int w = 0; w < 2; ++w)
