@@ -97,6 +97,9 @@ __device__ __forceinline__ uint2 lds_read_tr(const bf16_t* p) {
   return __builtin_bit_cast(uint2, v);
 }
 
+constexpr int kGroupRows = 4;      // row tiles per group of the tile order (ragged-row GEMMs) ...
+constexpr int kGroupMinCols = 12;  // ... used when the output has at least this many column tiles
+
 // A_KG / B_KG: the K-strided operand A / B takes its k-rows through the index table a_rows / b_rows (the dy rows,
 // or the input rows, of an expert's routed pairs)
 template <int MODE, int EPI, bool A_KC, bool B_KC, bool A_KG, bool B_KG, typename C>
@@ -124,8 +127,24 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
     logical = (long)(blockIdx.x % kXcds) * per_xcd + slot;
     if (slot >= per_xcd || logical >= total) return;
   }
-  const int nt = (int)(logical % gx);
-  const long mt_all = logical / gx;
+  int nt;
+  long mt_all;
+  if (MODE == kRaggedM && gx >= kGroupMinCols) {
+    // Row tiles are taken kGroupRows at a time and the column tiles run inside such a group, so that the 32 tiles an
+    // XCD works on at once are about kGroupRows row panels times 32/kGroupRows column panels: with the plain
+    // row-major order a wide output (many column tiles) has every CU of the XCD stream its own weight panel, and the
+    // next row tile of the expert streams them all again.
+    const long rows_all = total / gx;
+    const long per_group = (long)kGroupRows * gx;
+    const long grp_i = logical / per_group, within = logical - grp_i * per_group;
+    const long left = rows_all - grp_i * kGroupRows;
+    const int gm = (int)(left < kGroupRows ? left : kGroupRows);
+    nt = (int)(within / gm);
+    mt_all = grp_i * kGroupRows + within % gm;
+  } else {
+    nt = (int)(logical % gx);
+    mt_all = logical / gx;
+  }
 
   long m0, m_end, k_begin, k_end, b_group = 0, c_group = 0;
   bool ds_store2 = true;
