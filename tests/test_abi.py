@@ -69,6 +69,11 @@ def test_argument_checks_run_before_any_launch():
     assert lib.spes_moe_permute(ctypes.byref(ok_shape), p[0], p[1], None, None) == -1                   # no output
     assert lib.spes_moe_permute(ctypes.byref(ok_shape), p[0], p[1], _fake(0x20004), None) == -3         # misaligned output
     assert lib.spes_moe_permute(ctypes.byref(S.moe_shape(64, 60, 8, 64, 2, 1, 0)), p[0], p[1], p[2], None) == -2
+    lib.spes_ref_mfma_rate.restype = ctypes.c_int32
+    lib.spes_ref_mfma_rate.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    assert lib.spes_ref_mfma_rate(p[0], 0, 10, p[1], None, None) == -1                                   # no blocks
+    assert lib.spes_ref_mfma_rate(None, 4, 10, p[1], None, None) == -1                                   # no operands
+    assert lib.spes_ref_mfma_rate(_fake(0x30008), 4, 10, p[1], None, None) == -3                         # misaligned operands
     lib.spes_moe_router_aux.restype = ctypes.c_int32
     lib.spes_moe_router_aux.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_float, ctypes.c_float,
                                         ctypes.c_void_p, ctypes.c_void_p]

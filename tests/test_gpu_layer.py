@@ -113,3 +113,16 @@ def test_argument_errors(device):
     with pytest.raises(S.SpesError, match="invalid"):
         S.spes_moe_bwd(L.shape, L.dy, L.x, L.w_router, L.w_gate, L.w_up, L.w_down, L.ctx, L.mask, L.dx, L.d_w_router,
                        None, L.d_w_up, L.d_w_down)
+
+
+@pytest.mark.gpu
+def test_mfma_reference_loop_runs_and_counts_its_work():
+    """The benchmark's register-resident MFMA loop: launches, reports its operation count, and writes its sink."""
+    import paper_2602_11543_amd as S
+    dev = torch.device("cuda:0")
+    data = (torch.randn(32768, device=dev) * 0.02).to(torch.bfloat16)
+    sink = torch.full((8,), float("nan"), device=dev)
+    flop = S.spes_ref_mfma_rate(data, 8, 10, sink)
+    torch.cuda.synchronize()
+    assert flop == 8 * 4 * 10 * 16 * 2.0 * 32 * 32 * 16
+    assert bool(torch.isfinite(sink).all())
