@@ -49,7 +49,9 @@ typedef enum {
 typedef enum { SPES_F32 = 0, SPES_BF16 = 1 } spes_dtype;
 
 /* Shape of one routed feed-forward layer (Sec. 3.1 Eq. 2; Sec. 3.2).
- * Supported: 1 <= top_k <= n_experts <= 64; d_model and d_ff multiples of 8. */
+ * Supported: 1 <= top_k <= n_experts <= 64; d_model and d_ff multiples of 8;
+ * T*top_k below 2^22 - 4096; in bf16 storage T*d_model, T*top_k*d_ff and
+ * n_experts*d_ff*d_model each below 2^31 (SPES_ESHAPE otherwise). */
 typedef struct {
   int32_t T;           /* tokens in the batch                                         */
   int32_t d_model;     /* d                                                           */

@@ -32,6 +32,12 @@ int shape_supported(const spes_moe_shape* s) {
   if (s->d_model % 8 || s->d_ff % 8) return SPES_ESHAPE;
   const long R = (long)s->T * s->top_k;
   if (R > (1L << 22) - 4096) return SPES_ESHAPE;   // row-tile tables index a 16-bit grid dimension
+  if (s->dtype == SPES_BF16) {
+    // the matrix-core GEMMs address their operands with 32-bit byte offsets: x / dy, the saved and scratch [R,f]
+    // activations and the expert weight tensors must each stay below 2^31 elements
+    const long lim = 1L << 31;
+    if ((long)s->T * s->d_model >= lim || R * s->d_ff >= lim || (long)s->n_experts * s->d_ff * s->d_model >= lim) return SPES_ESHAPE;
+  }
   return SPES_OK;
 }
 

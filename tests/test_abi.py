@@ -56,6 +56,8 @@ def test_argument_checks_run_before_any_launch():
     assert fwd(S.moe_shape(64, 64, 8, 64, 2, 7, 0), p[:11]) == -1          # unknown dtype
     assert fwd(S.moe_shape(64, 64, 128, 64, 2, 1, 0), p[:11]) == -2        # more than 64 experts
     assert fwd(S.moe_shape(64, 60, 8, 64, 2, 1, 0), p[:11]) == -2          # d_model not a multiple of 8
+    assert fwd(S.moe_shape(1 << 20, 4096, 8, 64, 2, 1, 0), p[:11]) == -2   # x beyond the 32-bit operand offsets of the bf16 path
+    assert fwd(S.moe_shape(64, 8192, 64, 8192, 2, 1, 0), p[:11]) == -2     # expert weight tensor likewise
     nulls = list(p[:11]); nulls[5] = None
     assert fwd(ok_shape, nulls) == -1                                       # null y
     nulls = list(p[:11]); nulls[2] = None
