@@ -35,11 +35,13 @@ __global__ __launch_bounds__(256) void topk_gate_kernel(float* __restrict__ logi
   int my_idx = 0;
   float my_p = 0.f, psel = 0.f;
   for (int j = 0; j < k; ++j) {
-    float v = taken ? -INFINITY : s;
-    int i = lane;
-    wave_argmax(v, i);                     // selection on the scores: ties go to the lower expert id
+    // selection on the scores: the largest one not taken yet, and among equal scores the lowest lane, which is the
+    // lowest expert id (lanes beyond M hold -inf and M >= k, so a real expert is always found)
+    const float v = taken ? -INFINITY : s;
+    const float top = wave_max(v);
+    const int i = __ffsll((long long)__ballot(v == top && !taken)) - 1;
     if (lane == i) taken = true;
-    const float pw = __shfl(p, i, kWave);
+    const float pw = lane_value(p, i);
     psel += pw;
     if (lane == j) { my_idx = i; my_p = pw; }
   }
