@@ -204,15 +204,15 @@ __global__ __launch_bounds__(256) void gating_bwd_kernel(const float* __restrict
     const float mine = g * (dg - dot);
     // scatter lane j's value to lane sel
     for (int j = 0; j < k; ++j) {
-      const int ej = __shfl(sel, j, kWave);
-      const float vj = __shfl(mine, j, kWave);
+      const int ej = __builtin_amdgcn_readlane(sel, j);     // j is the same for the whole wavefront: scalar reads
+      const float vj = lane_value(mine, j);
       if (lane == ej) out = vj;
     }
   } else {
     float dp = 0.f;
     for (int j = 0; j < k; ++j) {
-      const int ej = __shfl(sel, j, kWave);
-      const float vj = __shfl(dg, j, kWave);
+      const int ej = __builtin_amdgcn_readlane(sel, j);
+      const float vj = lane_value(dg, j);
       if (lane == ej) dp = vj;
     }
     const float dot = wave_sum(dp * p);
