@@ -188,8 +188,10 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
   prof_mark(0, "softmax_topk", s);
   SPES_TRY(launch_routing_tables(topk_idx, topk_gate, (int)R, M, k, at<int>(ctx, L.block_counts), expert_count,
                                  at<int>(ctx, L.pub.offset), at<int>(ctx, L.pub.perm), at<int>(ctx, L.pub.inv),
-                                 at<int>(ctx, L.row_token), at<float>(ctx, L.row_gate), simt_row_tile(),
-                                 at<int>(ctx, L.tab_simt), mfma_row_tile(), at<int>(ctx, L.tab_mfma), L.max_tiles,
+                                 at<int>(ctx, L.row_token), at<float>(ctx, L.row_gate),
+                                 // only the row-tile table of the GEMM path this storage type runs on is built
+                                 dt == SPES_BF16 ? 0 : simt_row_tile(), at<int>(ctx, L.tab_simt),
+                                 dt == SPES_BF16 ? mfma_row_tile() : 0, at<int>(ctx, L.tab_mfma), L.max_tiles,
                                  at<float>(ctx, L.aux), s));
   prof_mark(0, "hist_scan_rank", s);
   // a = xp W_g^T, b = xp W_u^T, h = SiLU(a) * b with xp[r,:] = x[token of row r,:]: the GEMM reads its operand rows
