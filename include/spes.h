@@ -273,7 +273,7 @@ SPES_API int spes_ref_mfma_rate(const void* data, int32_t blocks, int32_t iters,
 
 /* Stage timing for benchmarks.  While enabled, spes_moe_fwd / spes_moe_bwd record a
  * HIP event on the caller's stream after each of their stages (the steps of the hot
- * path: router GEMM, softmax/top-k, histogram/scan/rank, permute, the grouped GEMMs,
+ * path: router GEMM, softmax/top-k, histogram/scan/rank, the grouped GEMMs,
  * combine, ...).  spes_profile_read waits for the last recorded event of the most
  * recent forward (which=0) or backward (which=1) and returns the number of stages,
  * filling ms[i] (milliseconds) and names[i] (static strings; names may be NULL) for
