@@ -56,6 +56,9 @@ def test_layer_parity(name, device):
     dict(T=200, d=128, M=8, f=128, k=1, bias="normal", bias_scale=8.0, dtype="bf16"),
     dict(T=96, d=8, M=8, f=8, k=2, n_trainable=8, dtype="bf16"),        # the smallest feature sizes the library takes
     dict(T=300, d=192, M=12, f=320, k=2, renorm=1, n_trainable=0, dtype="bf16"),
+    # outputs wide enough for the grouped tile order (at least 12 column tiles), with a ragged last group of row tiles
+    dict(T=700, d=64, M=5, f=1600, k=2, n_trainable=2, dtype="bf16"),
+    dict(T=700, d=3200, M=5, f=64, k=2, n_trainable=2, dtype="bf16"),
 ])
 def test_layer_edge_cases(kw, device):
     kw = dict(kw); kw.setdefault("router_sigma", 0.3)
