@@ -53,7 +53,10 @@ struct Cfg {
   static constexpr int PITCH = CH + 1;                      // row pitch in 16-byte units
   static constexpr int RP = 256 / CH;                       // rows staged per pass (K-contiguous operand)
   static constexpr int NA = BM / RP, NB = BN / RP;          // staging registers (uint4) per thread, K-contiguous
-  static constexpr int A_VEC = BM * PITCH, B_VEC = BN * PITCH;
+  static constexpr int KPA_ = BM / 8 + 4, KPB_ = BN / 8 + 4;
+  // an operand's LDS region holds either layout: [row][k] with a padded row, or [k][row] (below) with a padded k-row
+  static constexpr int A_VEC = BM * PITCH > BK * KPA_ ? BM * PITCH : BK * KPA_;
+  static constexpr int B_VEC = BN * PITCH > BK * KPB_ ? BN * PITCH : BK * KPB_;
   static constexpr int STAGE_VEC = A_VEC + B_VEC;
   // K-strided operand: [k][row] in LDS; a k-row of the tile is BM/8 (BN/8) chunks and 64 bytes of padding, so that
   // the four k-rows one transposing read touches start 16 banks apart
@@ -633,9 +636,11 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
 // one tile configuration: 256 x 256 x 64, one block per CU (144 KB of LDS, 256 accumulators per lane in AGPRs)
 typedef Cfg<256, 256, 64, 1> Tile;
 
-template <int MODE, int EPI, bool A_KC, bool B_KC, bool A_KG = false, bool B_KG = false>
+// narrow outputs (the router's M <= 64 expert columns): half the columns, so half the matrix work on padding
+typedef Cfg<256, 128, 64, 1> TileNarrow;
+
+template <int MODE, int EPI, bool A_KC, bool B_KC, bool A_KG = false, bool B_KG = false, typename C = Tile>
 int launch(const GemmArgs& g, hipStream_t s) {
-  typedef Tile C;
   static_assert(!A_KG || !A_KC, "k-row gather: K-strided A only");
   static_assert(!B_KG || (!B_KC && MODE == kGroupedK), "k-row gather of B: K-strided B of a grouped contraction only");
   static_assert(!(A_KG && B_KG), "one gathered operand per launch");
@@ -669,7 +674,9 @@ int launch_gemm_mfma(int mode, int epi, bool a_kcontig, bool b_kcontig, const Ge
     return SPES_EINVAL;
   }
   if (epi != kEpiStore) return SPES_EINVAL;
-  if (a_kcontig && b_kcontig) return launch<kGroupedK, kEpiStore, true, true>(g, s);
+  if (a_kcontig && b_kcontig)
+    return g.Ndim <= TileNarrow::BN ? launch<kGroupedK, kEpiStore, true, true, false, false, TileNarrow>(g, s)
+                                    : launch<kGroupedK, kEpiStore, true, true>(g, s);
   if (a_kcontig && !b_kcontig) return launch<kGroupedK, kEpiStore, true, false>(g, s);
   if (g.b_rows && (a_kcontig || b_kcontig || g.a_rows)) return SPES_EINVAL;
   if (!a_kcontig && !b_kcontig) {
