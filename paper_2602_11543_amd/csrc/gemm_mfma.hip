@@ -638,6 +638,8 @@ typedef Cfg<256, 256, 64, 1> Tile;
 
 // narrow outputs (the router's M <= 64 expert columns): half the columns, so half the matrix work on padding
 typedef Cfg<256, 128, 64, 1> TileNarrow;
+// few output rows (the router's weight gradient has M <= 64 of them)
+typedef Cfg<128, 256, 64, 1> TileShort;
 
 template <int MODE, int EPI, bool A_KC, bool B_KC, bool A_KG = false, bool B_KG = false, typename C = Tile>
 int launch(const GemmArgs& g, hipStream_t s) {
@@ -682,6 +684,7 @@ int launch_gemm_mfma(int mode, int epi, bool a_kcontig, bool b_kcontig, const Ge
   if (!a_kcontig && !b_kcontig) {
     if (g.a_rows) return launch<kGroupedK, kEpiStore, false, false, true>(g, s);
     if (g.b_rows) return launch<kGroupedK, kEpiStore, false, false, false, true>(g, s);
+    if (g.Mdim <= TileShort::BM) return launch<kGroupedK, kEpiStore, false, false, false, false, TileShort>(g, s);
     return launch<kGroupedK, kEpiStore, false, false>(g, s);
   }
   return SPES_EINVAL;
