@@ -640,6 +640,9 @@ typedef Cfg<256, 256, 64, 1> Tile;
 typedef Cfg<256, 128, 64, 1> TileNarrow;
 // few output rows (the router's weight gradient has M <= 64 of them)
 typedef Cfg<128, 256, 64, 1> TileShort;
+// a contraction of a single K-tile (the router's input gradient contracts over the M <= 64 experts) is all prologue
+// and epilogue: small tiles, two blocks per CU, so that one block's memory phases overlap the other's
+typedef Cfg<128, 128, 64, 2> TileSmall;
 
 template <int MODE, int EPI, bool A_KC, bool B_KC, bool A_KG = false, bool B_KG = false, typename C = Tile>
 int launch(const GemmArgs& g, hipStream_t s) {
@@ -679,7 +682,9 @@ int launch_gemm_mfma(int mode, int epi, bool a_kcontig, bool b_kcontig, const Ge
   if (a_kcontig && b_kcontig)
     return g.Ndim <= TileNarrow::BN ? launch<kGroupedK, kEpiStore, true, true, false, false, TileNarrow>(g, s)
                                     : launch<kGroupedK, kEpiStore, true, true>(g, s);
-  if (a_kcontig && !b_kcontig) return launch<kGroupedK, kEpiStore, true, false>(g, s);
+  if (a_kcontig && !b_kcontig)
+    return (g.kchunk <= TileSmall::BK && g.n_groups == 1) ? launch<kGroupedK, kEpiStore, true, false, false, false, TileSmall>(g, s)
+                                                          : launch<kGroupedK, kEpiStore, true, false>(g, s);
   if (g.b_rows && (a_kcontig || b_kcontig || g.a_rows)) return SPES_EINVAL;
   if (!a_kcontig && !b_kcontig) {
     if (g.a_rows) return launch<kGroupedK, kEpiStore, false, false, true>(g, s);
