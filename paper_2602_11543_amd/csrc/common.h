@@ -123,15 +123,6 @@ __device__ __forceinline__ int wave_sum_i(int v) {
   return v;
 }
 
-// (value, index) arg-max across the wave: larger value wins, equal values go to the lower index
-__device__ __forceinline__ void wave_argmax(float& v, int& i) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    float ov = __shfl_xor(v, o, kWave);
-    int oi = __shfl_xor(i, o, kWave);
-    if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
-  }
-}
 
 // block-wide sum for blockDim.x == 256; result valid in every thread
 __device__ __forceinline__ float block_sum_256(float v, float* smem4) {

@@ -80,7 +80,16 @@ __global__ __launch_bounds__(64) void gram_reduce_kernel(float* __restrict__ par
   const int i = blockIdx.x * 64 + threadIdx.x;
   if (i >= n) return;
   float acc = 0.f;
-  for (int p = 0; p < n_partial; ++p) acc += partial[(long)p * n + i];
+  // sixteen loads in flight at a time; the additions keep the order p = 0, 1, 2, ...
+  int p = 0;
+  for (; p + 16 <= n_partial; p += 16) {
+    float v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) v[u] = partial[(long)(p + u) * n + i];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) acc += v[u];
+  }
+  for (; p < n_partial; ++p) acc += partial[(long)p * n + i];
   partial[i] = acc;
 }
 
@@ -92,7 +101,7 @@ __global__ __launch_bounds__(256) void sim_topk_kernel(const float* __restrict__
   for (int i = tid; i < M * M; i += 256) G[i / M][i % M] = gram[i];
   __syncthreads();
   const int lane = tid & 63, w = tid >> 6;
-  for (int j = w; j < M; j += 4) {
+  for (int j = blockIdx.x * 4 + w; j < M; j += gridDim.x * 4) {     // one row per wavefront
     float a = -INFINITY;
     if (lane < M) {
       a = G[j][lane] / sqrtf(G[j][j] * G[lane][lane]);
@@ -102,9 +111,11 @@ __global__ __launch_bounds__(256) void sim_topk_kernel(const float* __restrict__
     bool taken = false;
     int mine = 0;
     for (int i = 0; i < K; ++i) {
-      float v = taken ? -INFINITY : a;
-      int ix = lane;
-      wave_argmax(v, ix);
+      // the largest similarity not taken yet; among equal ones the lowest lane, which is the lowest expert id
+      // (lanes beyond M and the row's own lane hold -inf, and K < M, so a real peer is always found)
+      const float v = taken ? -INFINITY : a;
+      const float top = wave_max(v);
+      const int ix = __ffsll((long long)__ballot(v == top && !taken)) - 1;
       if (lane == ix) taken = true;
       if (lane == i) mine = ix;
     }
@@ -207,7 +218,7 @@ int launch_sync_merge(int dtype, int n_experts, long elems, int n_nodes, const v
 
 int launch_sim_topk(float* partial, int n_partial, int M, int K, float* sim, int* nbr, hipStream_t s) {
   hipLaunchKernelGGL(gram_reduce_kernel, dim3(cdiv((long)M * M, 64)), dim3(64), 0, s, partial, n_partial, M * M);
-  hipLaunchKernelGGL(sim_topk_kernel, dim3(1), dim3(256), 0, s, partial, M, K, sim, nbr);
+  hipLaunchKernelGGL(sim_topk_kernel, dim3(cdiv(M, 4)), dim3(256), 0, s, partial, M, K, sim, nbr);
   return ok();
 }
 
