@@ -137,7 +137,7 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
 }
 
 inline int flat_grid(long total_vec) {
-  long b = (total_vec + 256L * 4 - 1) / (256L * 4);
+  long b = (total_vec + 255) / 256;       // one vector per thread where the grid allows it
   if (b < 1) b = 1;
   if (b > 1 << 20) b = 1 << 20;
   return (int)b;

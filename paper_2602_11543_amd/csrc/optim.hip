@@ -68,8 +68,8 @@ int launch_masked_adamw(int dtype, int n_experts, long elems, void* param, const
   h.inv_bc1 = (float)(1.0 / (1.0 - pow((double)beta1, (double)step)));
   h.inv_bc2 = (float)(1.0 / (1.0 - pow((double)beta2, (double)step)));
   const long nvec = elems / 4;
-  long gx = (nvec + 256L * 4 - 1) / (256L * 4);
-  gx = gx < 1 ? 1 : gx > 2048 ? 2048 : gx;
+  long gx = (nvec + 255) / 256;           // one vector per thread where the grid allows it
+  gx = gx < 1 ? 1 : gx > 8192 ? 8192 : gx;
   SlotTable tb;
   int n = 0;
   long slot = 0;

@@ -84,8 +84,8 @@ __global__ __launch_bounds__(256) void pack_kernel(const PackTable tb, uint4* __
 }
 
 inline int grid_x(long nvec) {
-  long b = (nvec + 256L * 4 - 1) / (256L * 4);
-  return (int)(b < 1 ? 1 : b > 4096 ? 4096 : b);
+  long b = (nvec + 255) / 256;            // one vector per thread where the grid allows it
+  return (int)(b < 1 ? 1 : b > 8192 ? 8192 : b);
 }
 
 }  // namespace
