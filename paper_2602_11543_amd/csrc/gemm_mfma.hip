@@ -679,6 +679,8 @@ int launch_gemm_mfma(int mode, int epi, bool a_kcontig, bool b_kcontig, const Ge
     return SPES_EINVAL;
   }
   if (epi != kEpiStore) return SPES_EINVAL;
+  if (a_kcontig && b_kcontig && g.Mdim <= TileSmall::BM && g.Ndim <= TileSmall::BN)      // the warm-up merge's Gram matrix
+    return launch<kGroupedK, kEpiStore, true, true, false, false, TileSmall>(g, s);
   if (a_kcontig && b_kcontig)
     return g.Ndim <= TileNarrow::BN ? launch<kGroupedK, kEpiStore, true, true, false, false, TileNarrow>(g, s)
                                     : launch<kGroupedK, kEpiStore, true, true>(g, s);
