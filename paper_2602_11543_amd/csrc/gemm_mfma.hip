@@ -569,8 +569,9 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
           float h[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) h[e] = a[e] * sigmoidf_(a[e]) * b[e];
-          *reinterpret_cast<float4*>(cat + ci) = av;
-          *reinterpret_cast<float4*>(cbt + ci) = bv;
+          // the saved projections are next read by the backward pass: streaming stores (h, which the next GEMM reads, stays plain)
+          store_stream(reinterpret_cast<float4*>(cat + ci), av);
+          store_stream(reinterpret_cast<float4*>(cbt + ci), bv);
           *reinterpret_cast<uint2*>(cht + ci) = make_uint2(pack2(h[0], h[1]), pack2(h[2], h[3]));
         }
       }
