@@ -313,3 +313,30 @@ def test_forward_is_per_token():
                         inp["w_down"], c.k, c.renorm)
     np.testing.assert_allclose(sub["y"], full["y"][pick], rtol=1e-13)
     assert np.array_equal(sub["idx"], full["idx"][pick])
+
+
+@pytest.mark.parametrize("renorm", [0, 1])
+def test_relabelling_the_experts_changes_nothing_but_the_labels(renorm):
+    # Eq. 2 sums over a set of experts: renaming them (router rows, bias and weights together) must leave y and dx
+    # alone and carry every per-expert result to its new name.  Catches an index used for the wrong tensor.
+    inp = _inputs(T=50, d=8, M=7, f=6, k=3, renorm=renorm, router_sigma=0.7, bias="normal", bias_scale=0.3)
+    c = inp["cfg"]
+    fwd = _fwd(inp)
+    bwd = _bwd(inp, fwd)
+    rng = np.random.default_rng(5)
+    new_of_old = rng.permutation(c.M)              # expert e is renamed new_of_old[e]
+    old_of_new = np.argsort(new_of_old)
+    x, dy = inp["x"], inp["dy"]
+    wr, bias = inp["w_router"][old_of_new], inp["router_bias"][old_of_new]
+    wg, wu, wd = inp["w_gate"][old_of_new], inp["w_up"][old_of_new], inp["w_down"][old_of_new]
+    f2 = O.moe_forward(x, wr, bias, wg, wu, wd, c.k, c.renorm, keep=True)
+    b2 = O.moe_backward(f2, dy, x, wr, wg, wu, wd, c.renorm)
+    assert np.array_equal(f2["idx"], new_of_old[fwd["idx"]])
+    np.testing.assert_allclose(f2["gate"], fwd["gate"], rtol=1e-13)
+    np.testing.assert_allclose(f2["y"], fwd["y"], rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(b2["dx"], bwd["dx"], rtol=1e-11, atol=1e-14)
+    np.testing.assert_allclose(b2["d_w_router"][new_of_old], bwd["d_w_router"], rtol=1e-11, atol=1e-14)
+    assert np.array_equal(f2["count"][new_of_old], fwd["count"])
+    for e in range(c.M):
+        np.testing.assert_allclose(b2["d_w_gate"][int(new_of_old[e])], bwd["d_w_gate"][e], rtol=1e-11, atol=1e-14)
+        np.testing.assert_allclose(b2["d_w_down"][int(new_of_old[e])], bwd["d_w_down"][e], rtol=1e-11, atol=1e-14)
