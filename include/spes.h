@@ -74,8 +74,8 @@ typedef struct {
   size_t offset;    /* [M+1] i32 first row of each expert in expert-contiguous order  */
   size_t perm;      /* [R] i32 row r holds routed pair perm[r] = t*k+j                */
   size_t inv;       /* [R] i32 inverse of perm                                        */
-  size_t a;         /* [R,f] f32 gate projection  W_g x (fp32: the gate gradient needs it) */
-  size_t b;         /* [R,f] f32 up projection    W_u x                                */
+  size_t a;         /* [R,f] gate projection  W_g x, in the storage type               */
+  size_t b;         /* [R,f] up projection    W_u x, in the storage type               */
   size_t h;         /* [R,f] SiLU(a)*b                                                */
   size_t yp;        /* [R,d] expert outputs before gating                             */
   size_t dlogits;   /* [T,M] f32, written by the backward                             */

@@ -234,7 +234,7 @@ def ctx_view(shape: spes_moe_shape, ctx: torch.Tensor, name: str) -> torch.Tenso
     st = torch_dtype(shape.dtype)
     spec = dict(logits=(torch.float32, (T, M)), lse=(torch.float32, (T,)), topk_idx=(torch.int32, (T, k)),
                 topk_gate=(torch.float32, (T, k)), offset=(torch.int32, (M + 1,)), perm=(torch.int32, (R,)),
-                inv=(torch.int32, (R,)), a=(torch.float32, (R, f)), b=(torch.float32, (R, f)), h=(st, (R, f)), yp=(st, (R, d)),
+                inv=(torch.int32, (R,)), a=(st, (R, f)), b=(st, (R, f)), h=(st, (R, f)), yp=(st, (R, d)),
                 dlogits=(torch.float32, (T, M)), dgate=(torch.float32, (T, k)))[name]
     n = int(np.prod(spec[1])) * torch.empty((), dtype=spec[0]).element_size()
     return ctx[lay[name]: lay[name] + n].view(spec[0]).view(spec[1])

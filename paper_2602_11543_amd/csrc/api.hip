@@ -14,7 +14,7 @@ constexpr int kRouterSplit = 64;   // chunks of the token axis in the router wei
 
 struct Layout {
   spes_moe_ctx_layout pub;
-  size_t block_counts, tab_simt, tab_mfma, row_token, row_gate, dgate_part, da, db, hg, dxp, wr_part, dlogits_bf, dxr, aux, aux_part;
+  size_t block_counts, tab_simt, tab_mfma, row_token, row_gate, hcorr, dgate_part, da, db, hg, dxp, wr_part, dlogits_bf, dxr, aux, aux_part;
   int max_tiles, max_tiles_mfma, max_col_tiles;
 };
 
@@ -61,8 +61,10 @@ Layout make_layout(const spes_moe_shape* s) {
   L.tab_mfma = take((1 + 2 * (size_t)L.max_tiles) * 4);
   L.row_token = take(R * 4);
   L.row_gate = take(R * 4);
-  L.pub.a = take(R * f * 4);
-  L.pub.b = take(R * f * 4);
+  // fp32 storage keeps the projections in fp32; bf16 storage keeps them in bf16 plus a bf16 correction of h
+  L.pub.a = take(R * f * (es == 4 ? 4 : 2));
+  L.pub.b = take(R * f * (es == 4 ? 4 : 2));
+  L.hcorr = take(es == 4 ? 0 : R * f * 2);
   L.pub.h = take(R * f * es);
   L.pub.yp = take(R * d * es);
   L.pub.dlogits = take(T * M * 4);
@@ -202,6 +204,7 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
     g.B[0] = w_gate; g.B[1] = w_up; g.b_ns = d; g.b_ks = 1; g.b_gs = (long)f * d; g.b_elems = (long)M * f * d;
     g.Kdim = d; g.Ndim = f;
     g.C[0] = at<void>(ctx, L.pub.a); g.C[1] = at<void>(ctx, L.pub.b); g.C[2] = at<void>(ctx, L.pub.h); g.c_ms = f;
+    g.C[3] = at<void>(ctx, L.hcorr);
     ragged_tables(g, ctx, L, dt);
     SPES_TRY(expert_gemm(dt, kRaggedM, kEpiSwiglu, true, true, g, s));
   }
@@ -277,7 +280,7 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
     g.A[0] = dy; g.a_ms = d; g.a_ks = 1; g.a_rows = at<int>(ctx, L.row_token); g.a_elems = (long)T * d;
     g.B[0] = w_down; g.b_ns = 1; g.b_ks = f; g.b_gs = (long)d * f; g.b_elems = (long)M * d * f;
     g.Kdim = d; g.Ndim = f;
-    g.E[0] = at<void>(ctx, L.pub.a); g.E[1] = at<void>(ctx, L.pub.b);
+    g.E[0] = at<void>(ctx, L.pub.a); g.E[1] = at<void>(ctx, L.pub.b); g.E[2] = at<void>(ctx, L.hcorr);
     g.C[0] = at<void>(ctx, L.da); g.C[1] = at<void>(ctx, L.db); g.C[2] = at<void>(ctx, L.hg); g.c_ms = f;
     g.row_scale = at<float>(ctx, L.row_gate);
     g.rowdot = at<float>(ctx, L.dgate_part); g.rowdot_stride = R;

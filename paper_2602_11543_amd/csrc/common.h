@@ -53,6 +53,11 @@ __device__ __forceinline__ void store_stream(float4* p, const float4& q) {
   const nt_f32x4_t v = {q.x, q.y, q.z, q.w};
   __builtin_nontemporal_store(v, reinterpret_cast<nt_f32x4_t*>(p));
 }
+__device__ __forceinline__ void store_stream(uint2* p, const uint2& q) {
+  typedef __attribute__((ext_vector_type(2))) unsigned int nt_u32x2_t;
+  const nt_u32x2_t v = {q.x, q.y};
+  __builtin_nontemporal_store(v, reinterpret_cast<nt_u32x2_t*>(p));
+}
 __device__ __forceinline__ void store_stream(uint4* p, const uint4& q) {
   const nt_u32x4_t v = {q.x, q.y, q.z, q.w};
   __builtin_nontemporal_store(v, reinterpret_cast<nt_u32x4_t*>(p));

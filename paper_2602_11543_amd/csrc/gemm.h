@@ -17,8 +17,10 @@ namespace spes {
 enum GemmMode { kRaggedM = 0, kGroupedK = 1 };
 enum GemmEpi {
   kEpiStore = 0,    // C[0] = acc (or += when accumulate)
-  kEpiSwiglu = 1,   // two accumulators a (pair 0), b (pair 1): C[0]=a (f32), C[1]=b (f32), C[2]=SiLU(a)*b
-  kEpiDSwiglu = 2   // acc = u (row of dy times W_d); with saved a=E[0], b=E[1] (f32), h = SiLU(a)*b:
+  kEpiSwiglu = 1,   // two accumulators a (pair 0), b (pair 1): C[0]=a, C[1]=b, C[2]=SiLU(a)*b.  Vector path: a, b in f32.
+                    // Matrix-core path: a, b rounded to bf16 and C[3] = bf16(h - SiLU(bf16 a)*(bf16 b)), so that the backward
+                    // has h to ~2^-17 from six bytes per element instead of eight
+  kEpiDSwiglu = 2   // acc = u (row of dy times W_d); with saved a=E[0], b=E[1] (and E[2], the correction above), h = SiLU(a)*b:
                     //   rowdot[tile_n][m] = sum_n u*h (the gate gradient), dh = row_scale[m]*u,
                     //   C[0] = da = dh*b*s(1+a(1-s)), C[1] = db = dh*a*s, s = sigmoid(a), C[2] = row_scale[m]*h
 };
@@ -36,8 +38,8 @@ struct GemmArgs {
   long b_ns, b_ks, b_gs;  // element strides of B along n, k, and per expert (kRaggedM)
   int npairs;             // kEpiStore/kEpiDSwiglu: (A,B) pairs accumulated into one result
   int Kdim;               // contraction length of each pair (kRaggedM) / total K (kGroupedK, uniform chunks)
-  void* C[3];
-  const void* E[2];
+  void* C[4];
+  const void* E[3];
   long c_ms;              // row stride of C and E (n stride is 1)
   long c_gs;              // per-group stride of C (kGroupedK)
   int c_f32;              // C is float whatever the storage type

@@ -470,22 +470,22 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   const int ds_r0 = wm * (BM / 2) + lane / DS_CPR;
   const bool ds_nin = ds_n < g.Ndim;
   const unsigned ds_ncl = ds_nin ? (unsigned)ds_n : 0u;
-  const float* ds_a = reinterpret_cast<const float*>(g.E[0]) + ds_tile;
-  const float* ds_b = reinterpret_cast<const float*>(g.E[1]) + ds_tile;
+  const bf16_t* ds_a = reinterpret_cast<const bf16_t*>(g.E[0]) + ds_tile;
+  const bf16_t* ds_b = reinterpret_cast<const bf16_t*>(g.E[1]) + ds_tile;
+  const bf16_t* ds_d = reinterpret_cast<const bf16_t*>(g.E[2]) + ds_tile;
   bf16_t* ds_c0 = reinterpret_cast<bf16_t*>(g.C[0]) + ds_tile;
   bf16_t* ds_c1 = reinterpret_cast<bf16_t*>(g.C[1]) + ds_tile;
   bf16_t* ds_c2 = reinterpret_cast<bf16_t*>(g.C[2]) + ds_tile;
-  float4 av[EPI == kEpiDSwiglu ? DS_HALF : 1][2], bv[EPI == kEpiDSwiglu ? DS_HALF : 1][2];
+  uint4 av[EPI == kEpiDSwiglu ? DS_HALF : 1], bv[EPI == kEpiDSwiglu ? DS_HALF : 1], dv[EPI == kEpiDSwiglu ? DS_HALF : 1];
   auto load_ab = [&](int i, int hf) {
     if (EPI == kEpiDSwiglu) {
 #pragma unroll
       for (int q = 0; q < DS_HALF; ++q) {
         const int rt = ds_r0 + i * 32 + (hf * DS_HALF + q) * DS_RPI;     // row within the tile
         const unsigned ci = (unsigned)(rt < ds_rows ? rt : ds_rows - 1) * (unsigned)g.c_ms + ds_ncl;
-        av[q][0] = *reinterpret_cast<const float4*>(ds_a + ci);
-        av[q][1] = *reinterpret_cast<const float4*>(ds_a + ci + 4);
-        bv[q][0] = *reinterpret_cast<const float4*>(ds_b + ci);
-        bv[q][1] = *reinterpret_cast<const float4*>(ds_b + ci + 4);
+        av[q] = *reinterpret_cast<const uint4*>(ds_a + ci);
+        bv[q] = *reinterpret_cast<const uint4*>(ds_b + ci);
+        dv[q] = *reinterpret_cast<const uint4*>(ds_d + ci);
       }
     }
   };
@@ -526,7 +526,10 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
       for (int gq = 0; gq < 4; ++gq) {
         // the dSwiGLU epilogue reads two adjacent 4-column groups per lane: even groups are kept in the first half
         // of the LDS row and odd groups in the second, so that each of its reads is contiguous across the lanes
-        const int col = (EPI == kEpiDSwiglu) ? lhalf * (ECOLS / 2) + (j * 4 + gq) * 4 : j * 32 + gq * 8 + lhalf * 4;
+        // (the SwiGLU epilogue does the same inside the gate half and inside the up half of its row)
+        const int col = (EPI == kEpiDSwiglu) ? lhalf * (ECOLS / 2) + (j * 4 + gq) * 4
+                      : (EPI == kEpiSwiglu)  ? (j / (TN / 2)) * (ECOLS / 2) + lhalf * (ECOLS / 4) + ((j % (TN / 2)) * 4 + gq) * 4
+                                             : j * 32 + gq * 8 + lhalf * 4;
         *reinterpret_cast<float4*>(ep + l32 * EPITCH + col) =
             make_float4(acc[j][i][gq * 4], acc[j][i][gq * 4 + 1], acc[j][i][gq * 4 + 2], acc[j][i][gq * 4 + 3]);
       }
@@ -549,30 +552,53 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
         }
       }
     } else if (EPI == kEpiSwiglu) {
-      // LDS columns [0, ECOLS/2) hold the gate projection, [ECOLS/2, ECOLS) the up projection of the same output columns
-      constexpr int CPR = ECOLS / 8, RPI = 64 / CPR;
-      const int c4 = lane % CPR;
-      const long n = n0 + wn * (BN / 4) + c4 * 4;
+      // LDS columns [0, ECOLS/2) hold the gate projection, [ECOLS/2, ECOLS) the up projection of the same output columns,
+      // each with its even 4-column groups first and its odd ones behind.  A lane takes eight output columns of a row
+      // (16-byte bf16 stores); the two rows that one 16-lane phase of a read touches are eight rows apart, which is 32
+      // banks with this pitch.
+      static_assert(EPI != kEpiSwiglu || (TN == 4 && ECOLS == 128), "lane layout of the SwiGLU epilogue");
+      const int c8 = lane & 7, rsel = lane >> 3;
+      const long n = n0 + wn * (BN / 4) + c8 * 8;
       const bool n_in = n < g.Ndim;
-      float* cat = reinterpret_cast<float*>(g.C[0]) + e_tile;
-      float* cbt = reinterpret_cast<float*>(g.C[1]) + e_tile;
+      bf16_t* cat = reinterpret_cast<bf16_t*>(g.C[0]) + e_tile;
+      bf16_t* cbt = reinterpret_cast<bf16_t*>(g.C[1]) + e_tile;
       bf16_t* cht = reinterpret_cast<bf16_t*>(g.C[2]) + e_tile;
+      bf16_t* cdt = reinterpret_cast<bf16_t*>(g.C[3]) + e_tile;
 #pragma unroll
-      for (int st = 0; st < 32 / RPI; ++st) {
-        const int row = st * RPI + lane / CPR;
-        const float4 av = *reinterpret_cast<const float4*>(ep + row * EPITCH + c4 * 4);
-        const float4 bv = *reinterpret_cast<const float4*>(ep + row * EPITCH + ECOLS / 2 + c4 * 4);
+      for (int st = 0; st < 4; ++st) {
+        const int row = (st >> 1) * 16 + (st & 1) * 4 + (rsel >> 1) + 8 * (rsel & 1);
+        const float* rp = ep + row * EPITCH + c8 * 4;
+        const float4 a0 = *reinterpret_cast<const float4*>(rp), a1 = *reinterpret_cast<const float4*>(rp + ECOLS / 4);
+        const float4 b0 = *reinterpret_cast<const float4*>(rp + ECOLS / 2), b1 = *reinterpret_cast<const float4*>(rp + 3 * ECOLS / 4);
         const int rt = e_r0 + i * 32 + row;
         if (rt < e_rows && n_in) {
           const unsigned ci = (unsigned)rt * (unsigned)g.c_ms + (unsigned)n;
-          const float a[4] = {av.x, av.y, av.z, av.w}, b[4] = {bv.x, bv.y, bv.z, bv.w};
-          float h[4];
+          const float a[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w}, b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+          // The backward needs a and b only to bf16 accuracy, but h = SiLU(a) b nearly to fp32 accuracy (its gate
+          // gradient is a difference of nearly equal sums when experts are near copies).  Saved are therefore a and b
+          // rounded to bf16 and the bf16 value of what the rounded pair misses, h - SiLU(bf16 a) (bf16 b): h comes back
+          // to about 2^-17 from six bytes per element instead of eight.  The miss is taken to first order in the two
+          // rounding steps (the second-order term is below 2^-18 of h), which needs no second sigmoid.
+          uint32_t ap[4], bp[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) h[e] = a[e] * sigmoidf_(a[e]) * b[e];
-          // the saved projections are next read by the backward pass: streaming stores (h, which the next GEMM reads, stays plain)
-          store_stream(reinterpret_cast<float4*>(cat + ci), av);
-          store_stream(reinterpret_cast<float4*>(cbt + ci), bv);
-          *reinterpret_cast<uint2*>(cht + ci) = make_uint2(pack2(h[0], h[1]), pack2(h[2], h[3]));
+          for (int e = 0; e < 4; ++e) { ap[e] = pack2(a[2 * e], a[2 * e + 1]); bp[e] = pack2(b[2 * e], b[2 * e + 1]); }
+          float h[8], dl[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float sg = sigmoidf_(a[e]);
+            const float sl = a[e] * sg;                               // SiLU(a)
+            h[e] = sl * b[e];
+            const float ar = __uint_as_float((e & 1) ? (ap[e >> 1] & 0xffff0000u) : (ap[e >> 1] << 16));
+            const float br = __uint_as_float((e & 1) ? (bp[e >> 1] & 0xffff0000u) : (bp[e >> 1] << 16));
+            const float dsl = sg + sl * (1.f - sg);                   // SiLU'(a)
+            dl[e] = dsl * (a[e] - ar) * br + sl * (b[e] - br);
+          }
+          // the saved values are next read by the backward pass: streaming stores (h, which the next GEMM reads, stays plain)
+          store_stream(reinterpret_cast<uint4*>(cat + ci), make_uint4(ap[0], ap[1], ap[2], ap[3]));
+          store_stream(reinterpret_cast<uint4*>(cbt + ci), make_uint4(bp[0], bp[1], bp[2], bp[3]));
+          store_stream(reinterpret_cast<uint4*>(cdt + ci),
+                       make_uint4(pack2(dl[0], dl[1]), pack2(dl[2], dl[3]), pack2(dl[4], dl[5]), pack2(dl[6], dl[7])));
+          *reinterpret_cast<uint4*>(cht + ci) = make_uint4(pack2(h[0], h[1]), pack2(h[2], h[3]), pack2(h[4], h[5]), pack2(h[6], h[7]));
         }
       }
     } else {
@@ -587,15 +613,22 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
           const float4 u1 = *reinterpret_cast<const float4*>(ep + row * EPITCH + ECOLS / 2 + ds_c8 * 4);
           const int rt = ds_r0 + i * 32 + (hf * DS_HALF + q) * DS_RPI;
           const float rs = g.row_scale[m0 + (rt < ds_rows ? rt : ds_rows - 1)];
-          const float u[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w},
-                      a[8] = {av[q][0].x, av[q][0].y, av[q][0].z, av[q][0].w, av[q][1].x, av[q][1].y, av[q][1].z, av[q][1].w},
-                      b[8] = {bv[q][0].x, bv[q][0].y, bv[q][0].z, bv[q][0].w, bv[q][1].x, bv[q][1].y, bv[q][1].z, bv[q][1].w};
+          const float u[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
+          const uint32_t aw[4] = {av[q].x, av[q].y, av[q].z, av[q].w}, bw[4] = {bv[q].x, bv[q].y, bv[q].z, bv[q].w},
+                         dw[4] = {dv[q].x, dv[q].y, dv[q].z, dv[q].w};
+          float a[8], b[8], hc[8];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            a[2 * e] = __uint_as_float(aw[e] << 16); a[2 * e + 1] = __uint_as_float(aw[e] & 0xffff0000u);
+            b[2 * e] = __uint_as_float(bw[e] << 16); b[2 * e + 1] = __uint_as_float(bw[e] & 0xffff0000u);
+            hc[2 * e] = __uint_as_float(dw[e] << 16); hc[2 * e + 1] = __uint_as_float(dw[e] & 0xffff0000u);
+          }
           float da[8], db[8], hg[8], dot = 0.f;
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
             const float sg = sigmoidf_(a[e]);
-            const float as = a[e] * sg;          // SiLU(a)
-            const float h = as * b[e];
+            const float as = a[e] * sg;          // SiLU of the saved (bf16) gate projection
+            const float h = as * b[e] + hc[e];   // the forward's h: what the rounded pair gives plus the saved correction
             dot = fmaf(u[e], h, dot);
             const float dh = rs * u[e];
             da[e] = dh * b[e] * (sg + as * (1.f - sg));
