@@ -58,6 +58,17 @@ __global__ __launch_bounds__(256) void gemm_simt_kernel(const GemmArgs g) {
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j) acc[p][i][j] = 0.f;
+  // Long contractions are summed in two levels: every kFlush K-tiles the running sums move into `total`, so the
+  // rounding error grows with sqrt(kFlush*BK) + sqrt(K / (kFlush*BK)) instead of sqrt(K).
+  constexpr int kFlush = 8;
+  float total[DUAL ? 2 : 1][4][4];
+#pragma unroll
+  for (int p = 0; p < (DUAL ? 2 : 1); ++p)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) total[p][i][j] = 0.f;
+  int since_flush = 0;
 
   const bool a_kfast = (g.a_ks == 1), b_kfast = (g.b_ks == 1);
   const int npass = DUAL ? 1 : g.npairs;
@@ -115,9 +126,24 @@ __global__ __launch_bounds__(256) void gemm_simt_kernel(const GemmArgs g) {
             for (int j = 0; j < 4; ++j) acc[p][i][j] = fmaf(a[i], b[j], acc[p][i][j]);
         }
       }
+      if (++since_flush == kFlush) {
+        since_flush = 0;
+#pragma unroll
+        for (int p = 0; p < (DUAL ? 2 : 1); ++p)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { total[p][i][j] += acc[p][i][j]; acc[p][i][j] = 0.f; }
+      }
       __syncthreads();
     }
   }
+#pragma unroll
+  for (int p = 0; p < (DUAL ? 2 : 1); ++p)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[p][i][j] += total[p][i][j];
 
   float dots[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
