@@ -274,11 +274,25 @@ def expert_weight_grads(e, fwd_routing, dy, x, w_gate_e, w_up_e, w_down_e):
     """
     idx, g = fwd_routing["idx"], fwd_routing["gate"]
     t_e, j_e = np.nonzero(idx == e)
-    x_e = _f64(x)[t_e]
+    x_e = _f64(np.asarray(x)[t_e])
     a, b, h, _ = expert_forward(x_e, w_gate_e, w_up_e, w_down_e)
-    dyp = g[t_e, j_e][:, None] * _f64(dy)[t_e]
+    dyp = g[t_e, j_e][:, None] * _f64(np.asarray(dy)[t_e])
     _, dwg, dwu, dwd = expert_backward(x_e, dyp, a, b, h, w_gate_e, w_up_e, w_down_e)
     return dwg, dwu, dwd
+
+
+def expert_gate_grads(e, fwd_routing, dy, x, w_gate_e, w_up_e, w_down_e):
+    """Gate gradients dgate[t,j] = <dy_t, E_e(x_t)> of the pairs routed to the single expert e (Eq. 2: the gate
+    multiplies the expert's output), from routing results only.
+
+    Returns (t_e, j_e, values): token and slot of each such pair and its gate gradient.  Visiting every expert fills
+    the whole dgate [T,k] without keeping any per-pair intermediate, which is how a large configuration gets its
+    router gradient checked.
+    """
+    idx = fwd_routing["idx"]
+    t_e, j_e = np.nonzero(idx == e)
+    _, _, _, yp = expert_forward(_f64(np.asarray(x)[t_e]), w_gate_e, w_up_e, w_down_e)
+    return t_e, j_e, np.einsum("nd,nd->n", _f64(np.asarray(dy)[t_e]), yp)
 
 
 # ----------------------------------------------------------------------------
@@ -322,11 +336,15 @@ def sync_merge(base, stores, slot, node_weight=None):
 
 
 def cosine_similarity(w_in):
-    """A[j,k] = <w_j, w_k> / (|w_j| |w_k|) over flattened input projections w_in [M,E]."""
+    """A[j,k] = <w_j, w_k> / (|w_j| |w_k|) over flattened input projections w_in [M,E] (Eq. 5).
+
+    Eq. 5 is undefined when an input projection is all zeros; the reading taken here gives such a pair the
+    similarity 0 (also on the diagonal), so a zero expert is nobody's preferred peer and everything stays finite."""
     w = _f64(w_in).reshape(w_in.shape[0], -1)
     G = w @ w.T
     n = np.sqrt(np.einsum("je,je->j", w, w))
-    return G / np.outer(n, n)
+    den = np.outer(n, n)
+    return np.divide(G, den, out=np.zeros_like(G), where=den > 0)
 
 
 def top_K_neighbours(A, K):

@@ -301,6 +301,14 @@ def test_mask_only_selects_which_weight_grads_exist():
         one = O.expert_weight_grads(e, fwd, inp["dy"], inp["x"], inp["w_gate"][e], inp["w_up"][e], inp["w_down"][e])
         np.testing.assert_allclose(one[0], full["d_w_gate"][e], rtol=1e-13, atol=1e-18)
         np.testing.assert_allclose(one[2], full["d_w_down"][e], rtol=1e-13, atol=1e-18)
+    # the gate gradient filled in one expert at a time equals the layer backward's, and with it the router gradient
+    dgate = np.full(full["dgate"].shape, np.nan)
+    for e in range(inp["cfg"].M):
+        t_e, j_e, v = O.expert_gate_grads(e, fwd, inp["dy"], inp["x"], inp["w_gate"][e], inp["w_up"][e], inp["w_down"][e])
+        dgate[t_e, j_e] = v
+    np.testing.assert_allclose(dgate, full["dgate"], rtol=1e-12, atol=1e-18)
+    dl = O.gating_backward(fwd["p"], fwd["idx"], fwd["gate"], dgate, inp["cfg"].renorm)
+    np.testing.assert_allclose(dl.T @ inp["x"].astype(np.float64), full["d_w_router"], rtol=1e-10, atol=1e-16)
 
 
 def test_forward_is_per_token():

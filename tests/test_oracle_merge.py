@@ -82,6 +82,27 @@ def test_cosine_similarity_properties_and_library():
     np.testing.assert_allclose(O.cosine_similarity(w3), O.cosine_similarity(w3.reshape(4, -1)))
 
 
+def test_zero_norm_projection_has_similarity_zero_and_is_never_preferred():
+    # Eq. 5 is 0/0 for an all-zero input projection; the reading: similarity 0 for every pair it is part of
+    rng = np.random.default_rng(11)
+    w = rng.standard_normal((6, 40))
+    ref = O.cosine_similarity(w)
+    w[3] = 0.0
+    A = O.cosine_similarity(w)
+    assert np.all(np.isfinite(A))
+    assert np.all(A[3] == 0.0) and np.all(A[:, 3] == 0.0)
+    keep = [0, 1, 2, 4, 5]
+    np.testing.assert_array_equal(A[np.ix_(keep, keep)], ref[np.ix_(keep, keep)])       # the other pairs are untouched
+    nbr = O.top_K_neighbours(A, 2)
+    assert nbr[3].tolist() == [0, 1]                                                     # all ties: lowest ids, never itself
+    for j in keep:                                                                       # 0 ranks between the positive and the negative ones
+        cand = sorted((k for k in range(6) if k != j), key=lambda k: (-A[j, k], k))
+        assert nbr[j].tolist() == cand[:2] and j not in nbr[j]
+    phi = rng.standard_normal((6, 12)); phi[3] = 0.0
+    out = O.warmup_merge(phi, nbr, 0.5)
+    np.testing.assert_allclose(out[3], 0.25 * (phi[0] + phi[1]), rtol=1e-14)             # Eq. 6 on the zero expert
+
+
 def test_top_K_neighbours_bruteforce():
     rng = np.random.default_rng(2)
     A = rng.standard_normal((9, 9)); A = (A + A.T) / 2
