@@ -6,7 +6,11 @@ of the hot path: router GEMM, softmax/top-k, histogram/scan/rank, dispatch, grou
 expert GEMMs, combine; backward with weight gradients for the trainable experts
 only) over one batch of seeded synthetic tokens already resident in HBM.  The
 dispatch copy is fused into the operand reads of the grouped GEMMs; its stand-alone
-kernel (spes_moe_permute) is timed beside the step and reported with in_step false.
+kernel (spes_moe_permute) and the stand-alone backward of the combine (spes_moe_grad_scatter) are timed beside the
+step and reported with in_step false.
+
+Without --config the headline is the largest single-GPU layer workload of the benchmark; the other layer workloads and
+the expert-merge sweep are timed after it with the same step counts and reported under other_workloads.
 
 Prints one JSON line: layer tokens/s, the roofline position of the dominant kernel
 (measured with HIP events recorded between stages on the launch stream), per-stage
@@ -78,6 +82,7 @@ def stage_model(cfg, rho_rows):
         "softmax_topk": ("hbm", T * M * 4 + 2 * R * 4 * 2 + T * 4),
         "hist_scan_rank": ("hbm", R * 4 * 7),
         "permute": ("hbm", T * d * s + R * d * s),
+        "grad_scatter": ("hbm", T * d * s + 2 * R * d * s + R * 12),      # dy once, yp rows in, scaled rows out, gate/inv/dgate
         "gemm_gate_up_swiglu": (mm, 4.0 * R * d * f),
         "gemm_down": (mm, 2.0 * R * d * f),
         "combine": ("hbm", R * d * s + T * d * s + R * 8),
@@ -94,7 +99,7 @@ def stage_model(cfg, rho_rows):
     }
 
 
-def bench_merge(args) -> int:
+def merge_figures(args) -> dict:
     """Expert synchronisation sweep (16 node copies of a 64-expert layer, d=2048, f=1024, bf16) and warm-up merge."""
     import numpy as np
     import torch
@@ -148,7 +153,11 @@ def bench_merge(args) -> int:
         S.spes_expert_warmup_merge(M, S.SPES_BF16, K, alpha, srcs[0], E, srcs, dsts, [E, E, E], sim, nbr, scratch)
 
     ms_warm = timed(warm_step, args.steps, args.warmup)
+    # similarity and peer selection alone (no matrix to mix): one pass over the input projections
+    ms_gram = timed(lambda: S.spes_expert_warmup_merge(M, S.SPES_BF16, K, alpha, srcs[0], E, [], [], [], sim, nbr, scratch),
+                    args.steps, args.warmup)
     bytes_warm = 2 * M * E + 3 * 2 * M * E * (K + 1 + 1)      # Gram pass + (K+1) reads and one write per matrix
+    bytes_warm_once = 2 * M * E + 3 * 2 * M * E * 2           # every matrix read once and written once (peer re-reads from cache)
     out = {"metric": "expert merge GB/s on 1 MI355X", "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "dtype": "bf16", "data": "synthetic",
            "config": {"workload": f"cfg5 merge: {nodes} nodes x {per} of {M} experts, d={d} f={f}, 3 matrices, weighted; "
@@ -157,9 +166,21 @@ def bench_merge(args) -> int:
                           "peak": PEAK_HBM_GBS, "frac": round(bytes_sync / ms_sync / 1e6 / PEAK_HBM_GBS, 4), "bound": "hbm"},
            "warmup_merge": {"ms": round(ms_warm, 4), "bytes": bytes_warm, "achieved": round(bytes_warm / ms_warm / 1e6, 1),
                             "peak": PEAK_HBM_GBS, "frac": round(bytes_warm / ms_warm / 1e6 / PEAK_HBM_GBS, 4), "bound": "hbm",
-                            "K": K, "alpha": alpha}}
+                            "K": K, "alpha": alpha,
+                            "similarity_pass": {"ms": round(ms_gram, 4), "bytes": 2 * M * E, "bound": "hbm",
+                                                "achieved": round(2 * M * E / ms_gram / 1e6, 1), "peak": PEAK_HBM_GBS,
+                                                "frac": round(2 * M * E / ms_gram / 1e6 / PEAK_HBM_GBS, 4)},
+                            "compulsory_bytes": bytes_warm_once,
+                            "achieved_compulsory": round(bytes_warm_once / ms_warm / 1e6, 1),
+                            "frac_compulsory": round(bytes_warm_once / ms_warm / 1e6 / PEAK_HBM_GBS, 4)}}
     out["value"] = out["sync_merge"]["achieved"]
-    print(json.dumps(out))
+    del mats, srcs, dsts, scratch
+    torch.cuda.empty_cache()
+    return out
+
+
+def bench_merge(args) -> int:
+    print(json.dumps(merge_figures(args)))
     return 0
 
 
@@ -171,8 +192,7 @@ def bench_train_step(args) -> int:
 
     import paper_2602_11543_amd as S
     from spes_workloads import CONFIGS, layer_inputs
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from harness import DeviceLayer
+    from paper_2602_11543_amd.layer import DeviceLayer
 
     cfg = CONFIGS[args.config]
     dev = torch.device("cuda:0")
@@ -277,40 +297,18 @@ def bench_init(args) -> int:
     return 0
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="cfg2", help="workload name from spes_workloads.CONFIGS")
-    ap.add_argument("--workload", default="layer", choices=["layer", "merge", "step", "init"],
-                    help="layer: fwd+bwd of the MoE layer (the headline metric); merge: expert synchronisation sweep; "
-                         "step: fwd + auxiliary losses + bwd + AdamW on the trainable subset; init: upcycling initialiser and upload packing")
-    ap.add_argument("--cpu-sample", type=int, default=16384, help="tokens of the workload timed through the fp64 oracle (0: skip)")
-    ap.add_argument("--graph", action="store_true", help="layer workload: replay the step from a captured HIP graph")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
-        return 2
-
-    if args.workload == "merge":
-        return bench_merge(args)
-    if args.workload == "step":
-        return bench_train_step(args)
-    if args.workload == "init":
-        return bench_init(args)
-
+def layer_figures(cfg_name: str, args, full: bool) -> dict:
+    """Times fwd + bwd of the layer workload `cfg_name`.  full: also the per-stage breakdown, the stand-alone dispatch and
+    gradient-scatter kernels, the matrix-rate reference and the CPU oracle; otherwise step time and stage durations only."""
     import numpy as np
     import torch
 
     import paper_2602_11543_amd as S
+    from paper_2602_11543_amd.layer import DeviceLayer
     from spes_workloads import CONFIGS, layer_inputs
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from harness import DeviceLayer
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
-    cfg = CONFIGS[args.config]
+    cfg = CONFIGS[cfg_name]
     t0 = time.time()
     inp = layer_inputs(cfg)
     L = DeviceLayer(inp, dev)
@@ -320,19 +318,21 @@ def main() -> int:
         L.fwd()
         L.bwd(0)
 
-    # a plain 1 GiB device copy: reference point for the HBM byte counters and for what a stream achieves here
-    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
-    dst = torch.empty_like(src)
-    dst.copy_(src)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(3):
-        dst.copy_(src)              # reads 1 GiB, writes 1 GiB
-    e1.record()
-    torch.cuda.synchronize()
-    copy_gbs = 3 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    del src, dst
+    copy_gbs = None
+    if full:
+        # a plain 1 GiB device copy: reference point for the HBM byte counters and for what a stream achieves here
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            dst.copy_(src)              # reads 1 GiB, writes 1 GiB
+        e1.record()
+        torch.cuda.synchronize()
+        copy_gbs = 3 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del src, dst
 
     run = step
     if args.graph:
@@ -369,24 +369,30 @@ def main() -> int:
             acc[n] = acc.get(n, 0.0) + ms
     S.spes_profile_enable(False)
     stage_ms = {n: v / args.steps for n, v in acc.items()}
-    # the dispatch copy is not part of the step (the grouped GEMMs read x through the routing table); its stand-alone
-    # kernel is timed here on the same stream, from the routing tables the last forward left in ctx
-    xp = torch.empty(cfg.T * cfg.k, cfg.d, dtype=L.x.dtype, device=dev)
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    S.spes_moe_permute(L.shape, L.x, L.ctx, xp)
-    ev[0].record()
-    for _ in range(args.steps):
-        S.spes_moe_permute(L.shape, L.x, L.ctx, xp)
-    ev[1].record()
-    torch.cuda.synchronize()
-    standalone = {"permute": ev[0].elapsed_time(ev[1]) / args.steps}
-    del xp
+    standalone = {}
+    if full:
+        # the dispatch copy and the gradient scatter are not part of the step (the grouped GEMMs read x and dy through the
+        # routing table); their stand-alone kernels are timed here on the same stream, from the record the last forward left
+        def timed_alone(fn):
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            fn()
+            ev[0].record()
+            for _ in range(args.steps):
+                fn()
+            ev[1].record()
+            torch.cuda.synchronize()
+            return ev[0].elapsed_time(ev[1]) / args.steps
+        xp = torch.empty(cfg.T * cfg.k, cfg.d, dtype=L.x.dtype, device=dev)
+        dgate = torch.empty(cfg.T, cfg.k, dtype=torch.float32, device=dev)
+        standalone["permute"] = timed_alone(lambda: S.spes_moe_permute(L.shape, L.x, L.ctx, xp))
+        standalone["grad_scatter"] = timed_alone(lambda: S.spes_moe_grad_scatter(L.shape, L.dy, L.ctx, xp, dgate))
+        del xp, dgate
 
     # what the matrix cores reach on this device with operand values like the workload's (the shader clock under
     # matrix load is power-limited and depends on the data): a register-resident MFMA loop, no memory traffic at all;
     # run after everything that is timed, so that it does not eat into their power budget
     mfma_tflops = None
-    if cfg.dtype == "bf16":
+    if full and cfg.dtype == "bf16":
         sink = torch.empty(256, dtype=torch.float32, device=dev)
         S.spes_ref_mfma_rate(L.w_gate, 256, 4000, sink)
         torch.cuda.synchronize()
@@ -432,10 +438,11 @@ def main() -> int:
                      "unit": dom["unit"], "frac": dom["frac"], "traffic": None},
         "grouped_gemm_util": {"flop": gemm_flop, "ms": round(gemm_ms, 4), "achieved_tflops": round(gemm_flop / (gemm_ms * 1e-3) / 1e12, 2),
                               "peak_tflops": gemm_peak, "frac": round(gemm_flop / (gemm_ms * 1e-3) / 1e12 / gemm_peak, 4)},
-        "hbm_copy_reference": {"achieved": round(copy_gbs, 1), "unit": "GB/s", "frac": round(copy_gbs / PEAK_HBM_GBS, 4),
-                               "what": "plain 1 GiB device-to-device copy (read + write bytes) on this GPU"},
         "stages": stages,
     }
+    if copy_gbs is not None:
+        out["hbm_copy_reference"] = {"achieved": round(copy_gbs, 1), "unit": "GB/s", "frac": round(copy_gbs / PEAK_HBM_GBS, 4),
+                                     "what": "plain 1 GiB device-to-device copy (read + write bytes) on this GPU"}
     if mfma_tflops is not None:
         out["mfma_reference"] = {"achieved": round(mfma_tflops, 1), "unit": "TFLOP/s", "frac_of_nominal": round(mfma_tflops / PEAK_BF16_TFLOPS, 4),
                                  "what": "register-resident 32x32x16 bf16 MFMA loop on this GPU, operands taken from the workload's expert "
@@ -446,7 +453,7 @@ def main() -> int:
         out["roofline"]["traffic"] = tr["bytes"]           # HBM-side bytes per launch (offline counters, see traffic_detail)
         out["roofline"]["traffic_detail"] = tr
 
-    if args.cpu_sample > 0:
+    if full and args.cpu_sample > 0:
         from oracle import spes_oracle as O
         n = min(args.cpu_sample, cfg.T)
         xs, dys = inp["x"][:n], inp["dy"][:n]
@@ -455,14 +462,65 @@ def main() -> int:
         O.moe_backward(fwd, dys, xs, inp["w_router"], inp["w_gate"], inp["w_up"], inp["w_down"], cfg.renorm,
                        wgrad_experts=L.trainable)
         cpu_s = time.perf_counter() - t0
+        del fwd
         try:
             from threadpoolctl import threadpool_info
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
         except Exception:
             cores = os.cpu_count()
         out["cpu_baseline"] = {"value": round(n / cpu_s, 1), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-                               "sample": f"fwd+bwd of the first {n} tokens of the workload through the fp64 numpy oracle "
+                               "sample": f"fwd+bwd of the first {n} of the workload's {cfg.T} tokens through the fp64 numpy oracle "
                                          f"(all {cfg.M} experts' weights, weight grads for the trainable ones), {cpu_s:.1f} s"}
+    del L, inp
+    torch.cuda.empty_cache()
+    return out
+
+
+HEADLINE = "cfg3"          # the largest of the benchmark's single-GPU layer workloads
+ALSO = ("cfg2", "cfg4", "cfg1")
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default=None,
+                    help=f"workload name from spes_workloads.CONFIGS; default: {HEADLINE} as the headline, and the other "
+                         f"benchmark workloads ({', '.join(ALSO)}, the cfg5 merge sweep) timed after it under `other_workloads`")
+    ap.add_argument("--workload", default="layer", choices=["layer", "merge", "step", "init"],
+                    help="layer: fwd+bwd of the MoE layer (the headline metric); merge: expert synchronisation sweep; "
+                         "step: fwd + auxiliary losses + bwd + AdamW on the trainable subset; init: upcycling initialiser and upload packing")
+    ap.add_argument("--cpu-sample", type=int, default=6144, help="tokens of the workload timed through the fp64 oracle (0: skip)")
+    ap.add_argument("--graph", action="store_true", help="layer workload: replay the step from a captured HIP graph")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    if args.workload == "merge":
+        return bench_merge(args)
+    if args.workload == "step":
+        args.config = args.config or "cfg2"
+        return bench_train_step(args)
+    if args.workload == "init":
+        return bench_init(args)
+
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    out = layer_figures(args.config or HEADLINE, args, full=True)
+    if args.config is None:
+        # every other workload of the benchmark, timed in the same run with the same step counts
+        others = {}
+        for name in ALSO:
+            o = layer_figures(name, args, full=False)
+            others[name] = {"workload": o["config"]["workload"], "tokens_per_s": o["value"], "ms_per_step": o["ms_per_step"],
+                            "dtype": o["dtype"], "grouped_gemm_util": o["grouped_gemm_util"],
+                            "roofline": {k: o["roofline"][k] for k in ("kernel", "bound", "achieved", "peak", "unit", "frac")},
+                            "stage_ms": {n: v["ms"] for n, v in o["stages"].items()}}
+        m = merge_figures(args)
+        others["cfg5_merge"] = {"workload": m["config"]["workload"], "sync_merge": m["sync_merge"], "warmup_merge": m["warmup_merge"]}
+        out["other_workloads"] = others
     print(json.dumps(out))
     return 0
 

@@ -11,8 +11,10 @@
  * Conventions that hold for every entry point
  *  - Plain C linkage, plain pointers and sizes.  "DEVICE" pointers address GPU
  *    memory of the current HIP device, "HOST" pointers ordinary host memory.
- *  - The library allocates no device memory and keeps no state between calls.
- *    Inputs, outputs, the context buffer and scratch are owned by the caller.
+ *  - The library allocates no device memory and the entry points declared here keep
+ *    no state between calls.  Inputs, outputs, the context buffer and scratch are
+ *    owned by the caller.  (The benchmark aids of spes_bench.h are the exception:
+ *    they hold a process-wide set of timing events.)
  *  - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
  *    the default stream).  No entry point synchronises or copies device memory
  *    back to the host; per-expert token counts are consumed on the device.
@@ -50,7 +52,7 @@ typedef enum { SPES_F32 = 0, SPES_BF16 = 1 } spes_dtype;
 
 /* Shape of one routed feed-forward layer (Sec. 3.1 Eq. 2; Sec. 3.2).
  * Supported: 1 <= top_k <= n_experts <= 64; d_model and d_ff multiples of 8;
- * T*top_k below 2^22 - 4096; in bf16 storage T*d_model, T*top_k*d_ff and
+ * T*top_k at most 2^22 - 4224; in bf16 storage T*d_model, T*top_k*d_ff and
  * n_experts*d_ff*d_model each below 2^31 (SPES_ESHAPE otherwise). */
 typedef struct {
   int32_t T;           /* tokens in the batch                                         */
@@ -119,6 +121,21 @@ SPES_API int spes_moe_fwd(const spes_moe_shape* shape, const void* x, const void
  */
 SPES_API int spes_moe_permute(const spes_moe_shape* shape, const void* x, const void* ctx, void* xp,
                               void* stream);
+
+/* Backward of the weighted combine of Eq. 2 as a stand-alone step: for the k routed pairs of
+ * every token,  dyp[inv[t*k+j], :] = gate[t,j] * dy[t, :]  (the upstream gradient of each routed
+ * row, in expert-contiguous order) and  dgate[t,j] = <dy[t, :], yp[inv[t*k+j], :]>  with yp the
+ * expert outputs the last spes_moe_fwd left in ctx.  spes_moe_bwd does not run this kernel: it
+ * gathers and scales the dy rows inside its first GEMM and takes the gate gradient from that
+ * GEMM's accumulators (yp is stored in the storage type; in bf16 that rounding is too coarse for
+ * the router gradient of near-identical experts).  This entry point materialises the step as the
+ * chain rule states it.
+ *
+ *  dy     DEVICE [T,d]                 ctx    DEVICE, as left by spes_moe_fwd for this shape
+ *  dyp    DEVICE [T*k, d] out          dgate  DEVICE [T,k] f32 out
+ */
+SPES_API int spes_moe_grad_scatter(const spes_moe_shape* shape, const void* dy, const void* ctx,
+                                   void* dyp, float* dgate, void* stream);
 
 /* Backward of the same layer for upstream gradient dy.  The selected expert set
  * is treated as constant.  The input gradient flows through every routed expert,
@@ -249,6 +266,8 @@ SPES_API int spes_expert_merge(int32_t n_experts, int64_t elems, int32_t dtype, 
  *  src,dst  HOST arrays of n_mats DEVICE pointers, matrix m is [M, elems[m]]
  *  elems    HOST  [n_mats], each a multiple of 8
  *  sim      DEVICE [M,M] f32 out or NULL;  nbr DEVICE [M,top_K] i32 out
+ *           (a pair with a zero-norm projection, for which Eq. 5 is 0/0, gets similarity 0;
+ *           every entry of nbr is a valid expert other than the row's own, whatever w_in holds)
  *  scratch  DEVICE, spes_warmup_scratch_bytes(M, elems_in) bytes
  */
 SPES_API size_t spes_warmup_scratch_bytes(int32_t n_experts, int64_t elems_in);
@@ -257,31 +276,6 @@ SPES_API int spes_expert_warmup_merge(int32_t n_experts, int32_t dtype, int32_t 
                                       const void* const* src, void* const* dst,
                                       const int64_t* elems, float* sim, int32_t* nbr,
                                       void* scratch, void* stream);
-
-/* Reference rate of the matrix cores, for benchmarks: launches `blocks` workgroups of four
- * wavefronts that each run `iters` rounds of sixteen 32x32x16 bf16 MFMAs on operands held in
- * registers, taken from `data`.  The shader clock under matrix load depends on the operand
- * values (power), so the rate to compare a GEMM with is this loop timed on values like the
- * GEMM's.  The caller times the launch (events on `stream`); *flop receives the number of
- * floating-point operations it performs.
- *
- *  data   DEVICE, 64 KiB of bf16 operand values     sink  DEVICE [blocks] f32 out (no meaning)
- *  flop   HOST out, may be NULL
- */
-SPES_API int spes_ref_mfma_rate(const void* data, int32_t blocks, int32_t iters, float* sink,
-                                double* flop, void* stream);
-
-/* Stage timing for benchmarks.  While enabled, spes_moe_fwd / spes_moe_bwd record a
- * HIP event on the caller's stream after each of their stages (the steps of the hot
- * path: router GEMM, softmax/top-k, histogram/scan/rank, the grouped GEMMs,
- * combine, ...).  spes_profile_read waits for the last recorded event of the most
- * recent forward (which=0) or backward (which=1) and returns the number of stages,
- * filling ms[i] (milliseconds) and names[i] (static strings; names may be NULL) for
- * at most cap stages.  The events are the library's only process-wide state; calls
- * that overlap on several streams while timing is enabled overwrite each other's
- * records.  Not meant for production paths. */
-SPES_API int spes_profile_enable(int32_t on);
-SPES_API int spes_profile_read(int32_t which, float* ms, const char** names, int32_t cap);
 
 SPES_API const char* spes_strerror(int code);
 

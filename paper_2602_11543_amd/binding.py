@@ -1,7 +1,7 @@
 """ctypes binding of libspes.so: argument marshalling only.
 
 Every function has the name and argument order of its C entry point in
-include/spes.h and takes torch tensors (device memory) or numpy arrays (host
+include/spes.h (include/spes_bench.h for the benchmark aids) and takes torch tensors (device memory) or numpy arrays (host
 arrays) in place of raw pointers.  Nothing is computed here; if the library is
 missing and cannot be built the import fails loudly -- there is no fallback.
 """
@@ -51,6 +51,8 @@ def _load() -> ctypes.CDLL:
     lib.spes_moe_bwd.argtypes = [shp] + [vp] * 13 + [i32, vp]
     lib.spes_moe_permute.restype = i32
     lib.spes_moe_permute.argtypes = [shp, vp, vp, vp, vp]
+    lib.spes_moe_grad_scatter.restype = i32
+    lib.spes_moe_grad_scatter.argtypes = [shp, vp, vp, vp, vp, vp]
     lib.spes_moe_router_aux.restype = i32
     lib.spes_moe_router_aux.argtypes = [shp, vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, vp, vp]
     lib.spes_masked_adamw.restype = i32
@@ -143,6 +145,11 @@ def spes_moe_bwd(shape, dy, x, w_router, w_gate, w_up, w_down, ctx, trainable_ma
 
 def spes_moe_permute(shape, x, ctx, xp, stream=None) -> None:
     _check(_lib.spes_moe_permute(ctypes.byref(shape), _dev(x), _dev(ctx), _dev(xp), _stream(stream)), "spes_moe_permute")
+
+
+def spes_moe_grad_scatter(shape, dy, ctx, dyp, dgate, stream=None) -> None:
+    _check(_lib.spes_moe_grad_scatter(ctypes.byref(shape), _dev(dy), _dev(ctx), _dev(dyp), _dev(dgate), _stream(stream)),
+           "spes_moe_grad_scatter")
 
 
 def spes_moe_router_aux(shape, ctx, lb_coef, z_coef, grad_scale, losses, stream=None) -> None:

@@ -31,7 +31,9 @@ int shape_supported(const spes_moe_shape* s) {
   if (s->n_experts > kMaxExperts) return SPES_ESHAPE;
   if (s->d_model % 8 || s->d_ff % 8) return SPES_ESHAPE;
   const long R = (long)s->T * s->top_k;
-  if (R > (1L << 22) - 4096) return SPES_ESHAPE;   // row-tile tables index a 16-bit grid dimension
+  // the row tiles of the vector-ALU GEMMs (64 rows each, at most one partly filled tile per expert) are a grid
+  // dimension of at most 65535
+  if (R / 64 + kMaxExperts + 1 > 65535) return SPES_ESHAPE;
   if (s->dtype == SPES_BF16) {
     // the matrix-core GEMMs address their operands with 32-bit byte offsets: x / dy, the saved and scratch [R,f]
     // activations and the expert weight tensors must each stay below 2^31 elements
@@ -234,6 +236,17 @@ SPES_API int spes_moe_permute(const spes_moe_shape* shape, const void* x, const 
                         static_cast<hipStream_t>(stream));
 }
 
+SPES_API int spes_moe_grad_scatter(const spes_moe_shape* shape, const void* dy, const void* ctx, void* dyp, float* dgate,
+                                   void* stream) {
+  SPES_TRY(shape_supported(shape));
+  if (!dy || !ctx || !dyp || !dgate) return SPES_EINVAL;
+  if (!aligned16(dy) || !aligned16(ctx) || !aligned16(dyp) || !aligned16(dgate)) return SPES_EALIGN;
+  const Layout L = make_layout(shape);
+  void* c = const_cast<void*>(ctx);
+  return launch_grad_scatter(shape->dtype, dy, at<void>(c, L.pub.yp), at<int>(c, L.pub.inv), at<float>(c, L.pub.topk_gate), dyp,
+                             dgate, shape->T, shape->d_model, shape->top_k, static_cast<hipStream_t>(stream));
+}
+
 SPES_API int spes_moe_router_aux(const spes_moe_shape* shape, void* ctx, float lb_coef, float z_coef, float grad_scale,
                                  float* losses, void* stream) {
   SPES_TRY(shape_supported(shape));
@@ -427,9 +440,11 @@ SPES_API int spes_expert_merge(int32_t n_experts, int64_t elems, int32_t dtype, 
                            static_cast<hipStream_t>(stream));
 }
 
+// chunks of the long contraction of the Gram matrix, one partial sum each
+constexpr int kMaxGramGroups = 512;
 static int gram_groups(int64_t elems_in) {
-  long g = (elems_in + 8191) / 8192;
-  if (g > 1024) g = 1024;
+  long g = (elems_in + 4095) / 4096;
+  if (g > kMaxGramGroups) g = kMaxGramGroups;
   if (g < 1) g = 1;
   return (int)g;
 }
@@ -457,16 +472,17 @@ SPES_API int spes_expert_warmup_merge(int32_t n_experts, int32_t dtype, int32_t 
   const int M = n_experts;
   const int ng = gram_groups(elems_in);
   const long kchunk = ((elems_in + ng - 1) / ng + 63) / 64 * 64;   // whole K-tiles per group
-  {
-    // Gram matrix of the flattened input projections, split along the long contraction
+  if (dtype == SPES_BF16) {
+    // Gram matrix of the flattened input projections: one streaming pass, a partial sum per chunk of the long contraction
+    SPES_TRY(launch_gram_bf16(w_in, M, elems_in, ng, kchunk, static_cast<float*>(scratch), s));
+  } else {
     GemmArgs g = blank();
     g.A[0] = w_in; g.a_ms = elems_in; g.a_ks = 1; g.a_elems = (long)n_experts * elems_in;
     g.B[0] = w_in; g.b_ns = elems_in; g.b_ks = 1; g.b_elems = (long)n_experts * elems_in;
     g.Kdim = (int)elems_in; g.kchunk = (int)kchunk; g.n_groups = ng;
     g.Mdim = M; g.Ndim = M;
     g.C[0] = scratch; g.c_ms = M; g.c_gs = (long)M * M; g.c_f32 = 1;
-    if (dtype == SPES_BF16 && M % 4 == 0) SPES_TRY(launch_gemm_mfma(kGroupedK, kEpiStore, true, true, g, s));
-    else SPES_TRY(launch_gemm_simt(dtype, dtype, kGroupedK, kEpiStore, g, s));
+    SPES_TRY(launch_gemm_simt(dtype, dtype, kGroupedK, kEpiStore, g, s));
   }
   SPES_TRY(launch_sim_topk(static_cast<float*>(scratch), ng, M, top_K, sim, nbr, s));
   for (int m = 0; m < n_mats; ++m)

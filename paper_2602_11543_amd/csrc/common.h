@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #include "../../include/spes.h"
+#include "../../include/spes_bench.h"
 
 namespace spes {
 

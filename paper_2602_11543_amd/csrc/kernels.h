@@ -25,13 +25,17 @@ int launch_combine(int dtype, const void* yp, const int* inv, const float* gate,
 int launch_dx_gather(int dtype, const void* dxp, const int* inv, const float* dlogits, const void* w_router, const void* dxr,
                      void* dx, int T, int d, int k, int M, hipStream_t s);
 
+// dyp[inv[t*k+j],:] = gate[t,j] * dy[t,:], dgate[t,j] = <dy[t,:], yp[inv[t*k+j],:]> (movement.hip)
+int launch_grad_scatter(int dtype, const void* dy, const void* yp, const int* inv, const float* gate, void* dyp, float* dgate,
+                        int T, int d, int k, hipStream_t s);
+
 // out[i] (+)= sum_p partial[p*n + i], p ascending (movement.hip)
 int launch_reduce_partials(const float* partial, int n_partial, long n, float* out, int accumulate, hipStream_t s);
 
 // merge.hip
-struct MergeSrc;
 int launch_sync_merge(int dtype, int n_experts, long elems, int n_nodes, const void* const* node_store, const int* slot,
                       const float* node_weight, void* dst, int* trainer_count, hipStream_t s);
+int launch_gram_bf16(const void* w, int M, long elems, int n_groups, long kchunk, float* partial, hipStream_t s);
 int launch_sim_topk(float* partial, int n_partial, int M, int K, float* sim, int* nbr, hipStream_t s);
 int launch_warmup_mix(int dtype, int M, long elems, int K, float alpha, const void* src, void* dst, const int* nbr, hipStream_t s);
 

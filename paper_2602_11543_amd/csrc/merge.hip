@@ -75,6 +75,72 @@ __global__ void write_counts_kernel(const CountTable tb, int* __restrict__ train
   if (i < tb.n) trainer_count[tb.base + i] = tb.c[i];
 }
 
+// Gram matrix of up to 64 bf16 rows, G = W W^T, as partial sums over chunks of the (long) row length: a pure stream of
+// the matrix, read once (Eq. 5: all pairwise inner products of the flattened input projections).
+// Both operands of every product are the same data, so nothing is staged: lane l of a wavefront loads the sixteen bytes
+// of row l%32 (+32 for the second fragment) that a 32x32x16 MFMA expects at k = (l/32)*8 .. +8 of a 16-wide k-step, and
+// the two fragments feed all four 32x32 blocks of the 64x64 result.  Register r of lane l of block (i,j) holds
+// G[32i + (r/4)*8 + (l/32)*4 + r%4][32j + l%32].  The four wavefronts of a block take a quarter of the block's chunk
+// each and are added in wavefront order through LDS; the block partials are added in block order by gram_reduce_kernel.
+typedef __attribute__((ext_vector_type(8))) __bf16 gram_bf16x8;
+typedef __attribute__((ext_vector_type(16))) float gram_f32x16;
+constexpr int kGramUnroll = 8;      // k-steps requested together: sixteen 16-byte loads per lane in flight
+constexpr int kGramPitch = 65;      // floats per LDS row (odd: the two row groups of a store fall into different banks)
+
+__global__ __launch_bounds__(256, 2) void gram_bf16_kernel(const bf16_t* __restrict__ w, int M, long elems, long kchunk,
+                                                           float* __restrict__ partial) {
+  __shared__ float red[4][64 * kGramPitch];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int row = lane & 31, half = lane >> 5;
+  const long c0 = (long)blockIdx.x * kchunk;
+  const long c1 = c0 + kchunk < elems ? c0 + kchunk : elems;
+  const long quarter = kchunk / 4;                       // a multiple of 16: k-steps never straddle two wavefronts
+  const long k0 = c0 + wave * quarter;
+  const long k1 = k0 + quarter < c1 ? k0 + quarter : c1;
+  const bool r0_in = row < M, r1_in = row + 32 < M;
+  const bf16_t* p0 = w + (long)(r0_in ? row : 0) * elems + half * 8;
+  const bf16_t* p1 = w + (long)(r1_in ? row + 32 : 0) * elems + half * 8;
+  gram_f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  for (long k = k0; k < k1; k += 16 * kGramUnroll) {
+    uint4 f0[kGramUnroll], f1[kGramUnroll];
+#pragma unroll
+    for (int u = 0; u < kGramUnroll; ++u) {
+      const long kk = k + u * 16 + half * 8;             // this lane's eight elements of k-step u (elems is a multiple of 8)
+      const bool in = kk < k1;
+      f0[u] = (in && r0_in) ? load_stream(reinterpret_cast<const uint4*>(p0 + k + u * 16)) : make_uint4(0, 0, 0, 0);
+      f1[u] = (in && r1_in) ? load_stream(reinterpret_cast<const uint4*>(p1 + k + u * 16)) : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < kGramUnroll; ++u) {
+      const gram_bf16x8 a = __builtin_bit_cast(gram_bf16x8, f0[u]), b = __builtin_bit_cast(gram_bf16x8, f1[u]);
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, a, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, b, acc[1][1], 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        red[wave][(32 * i + (r / 4) * 8 + half * 4 + r % 4) * kGramPitch + 32 * j + row] = acc[i][j][r];
+  __syncthreads();
+  float* out = partial + (long)blockIdx.x * M * M;
+  for (int e = tid; e < M * M; e += 256) {
+    const int i = e / M, j = e - i * M;
+    const int at = i * kGramPitch + j;
+    out[e] = ((red[0][at] + red[1][at]) + red[2][at]) + red[3][at];
+  }
+}
+
 // Sum the Gram partials in a fixed order: entry i of the result lands in partial 0.
 __global__ __launch_bounds__(64) void gram_reduce_kernel(float* __restrict__ partial, int n_partial, int n) {
   const int i = blockIdx.x * 64 + threadIdx.x;
@@ -93,7 +159,10 @@ __global__ __launch_bounds__(64) void gram_reduce_kernel(float* __restrict__ par
   partial[i] = acc;
 }
 
-// Normalise the Gram matrix to cosines and pick each row's top-K peers.
+// Normalise the Gram matrix to cosines and pick each row's top-K peers.  Eq. 5 is undefined for an expert whose
+// input projection has zero norm; such a pair gets similarity 0.  Whatever the Gram matrix holds (a NaN from
+// non-finite weights included), every peer written is a valid expert other than the row's own: the mix kernel
+// indexes the store with it.
 __global__ __launch_bounds__(256) void sim_topk_kernel(const float* __restrict__ gram, int M, int K,
                                                        float* __restrict__ sim, int* __restrict__ nbr) {
   __shared__ float G[kMaxExperts][kMaxExperts + 1];
@@ -102,20 +171,23 @@ __global__ __launch_bounds__(256) void sim_topk_kernel(const float* __restrict__
   __syncthreads();
   const int lane = tid & 63, w = tid >> 6;
   for (int j = blockIdx.x * 4 + w; j < M; j += gridDim.x * 4) {     // one row per wavefront
+    const bool valid = lane < M && lane != j;                       // lanes that may be chosen as a peer of j
     float a = -INFINITY;
     if (lane < M) {
-      a = G[j][lane] / sqrtf(G[j][j] * G[lane][lane]);
+      const float den = G[j][j] * G[lane][lane];
+      a = den > 0.f ? G[j][lane] / sqrtf(den) : 0.f;
       if (sim != nullptr) sim[j * M + lane] = a;
-      if (lane == j) a = -INFINITY;
+      if (!(a == a)) a = -INFINITY;                                 // a NaN ranks below every number
     }
     bool taken = false;
     int mine = 0;
     for (int i = 0; i < K; ++i) {
-      // the largest similarity not taken yet; among equal ones the lowest lane, which is the lowest expert id
-      // (lanes beyond M and the row's own lane hold -inf, and K < M, so a real peer is always found)
-      const float v = taken ? -INFINITY : a;
+      // the largest similarity not taken yet; among equal ones the lowest lane, which is the lowest expert id.
+      // K < M, so at least one valid lane is still free, and a free valid lane always matches the maximum
+      // taken over the free valid lanes
+      const float v = (valid && !taken) ? a : -INFINITY;
       const float top = wave_max(v);
-      const int ix = __ffsll((long long)__ballot(v == top && !taken)) - 1;
+      const int ix = __ffsll((long long)__ballot(valid && !taken && v == top)) - 1;
       if (lane == ix) taken = true;
       if (lane == i) mine = ix;
     }
@@ -215,6 +287,13 @@ int launch_sync_merge(int dtype, int n_experts, long elems, int n_nodes, const v
     if (ok() != SPES_OK) return SPES_EHIP;
   }
   return SPES_OK;
+}
+
+// partial[b][M*M], b < n_groups: Gram partial of columns [b*kchunk, (b+1)*kchunk) of the bf16 matrix w [M, elems]
+int launch_gram_bf16(const void* w, int M, long elems, int n_groups, long kchunk, float* partial, hipStream_t s) {
+  if (M > 64 || kchunk % 64 != 0 || elems % 8 != 0) return SPES_ESHAPE;
+  hipLaunchKernelGGL(gram_bf16_kernel, dim3(n_groups), dim3(256), 0, s, (const bf16_t*)w, M, elems, kchunk, partial);
+  return ok();
 }
 
 int launch_sim_topk(float* partial, int n_partial, int M, int K, float* sim, int* nbr, hipStream_t s) {

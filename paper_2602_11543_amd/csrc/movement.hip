@@ -122,6 +122,74 @@ __global__ __launch_bounds__(256) void dx_gather_kernel(const T* __restrict__ dx
   }
 }
 
+// Backward of the weighted combine as a stand-alone step: for the k routed pairs of token t,
+// dyp[inv[t*k+j], :] = gate[t,j] * dy[t, :] and dgate[t,j] = <dy[t, :], yp[inv[t*k+j], :]>.  One block per token: the
+// token's dy row is read once and its k scaled copies written, the k rows of yp are read once for the dots.
+// KU > 0: k == KU, the thread's k rows of yp are all requested before the first is used.
+template <typename T, int KU>
+__global__ __launch_bounds__(256) void grad_scatter_kernel(const T* __restrict__ dy, const T* __restrict__ yp,
+                                                           const int* __restrict__ inv, const float* __restrict__ gate,
+                                                           T* __restrict__ dyp, float* __restrict__ dgate, int d, int k) {
+  constexpr int N = Vec16<T>::N;
+  __shared__ int rows[kMaxExperts];
+  __shared__ float gts[kMaxExperts];
+  __shared__ float part[kMaxExperts][4];
+  const long t = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  if (tid < k) { rows[tid] = inv[t * k + tid]; gts[tid] = gate[t * k + tid]; }
+  __syncthreads();
+  const int nvec = d / N;
+  if (KU > 0) {
+    float dots[KU > 0 ? KU : 1];
+#pragma unroll
+    for (int j = 0; j < KU; ++j) dots[j] = 0.f;
+    for (int c = tid; c < nvec; c += 256) {
+      Vec16<T> q, qy[KU > 0 ? KU : 1];
+      q.load_once(dy + t * d + c * N);
+#pragma unroll
+      for (int j = 0; j < KU; ++j) qy[j].load_once(yp + (long)rows[j] * d + c * N);
+      float g[N];
+      q.unpack(g);
+#pragma unroll
+      for (int j = 0; j < KU; ++j) {
+        float f[N], o[N];
+        qy[j].unpack(f);
+#pragma unroll
+        for (int i = 0; i < N; ++i) { dots[j] = fmaf(g[i], f[i], dots[j]); o[i] = gts[j] * g[i]; }
+        Vec16<T> w;
+        w.pack(o);
+        w.store_once(dyp + (long)rows[j] * d + c * N);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < KU; ++j) {
+      const float v = wave_sum(dots[j]);
+      if (lane == 0) part[j][wv] = v;
+    }
+  } else {
+    for (int j = 0; j < k; ++j) {
+      float dot = 0.f;
+      for (int c = tid; c < nvec; c += 256) {
+        Vec16<T> q, qy;
+        q.load(dy + t * d + c * N);                    // read again for the next pair: from the cache
+        qy.load_once(yp + (long)rows[j] * d + c * N);
+        float g[N], f[N], o[N];
+        q.unpack(g);
+        qy.unpack(f);
+#pragma unroll
+        for (int i = 0; i < N; ++i) { dot = fmaf(g[i], f[i], dot); o[i] = gts[j] * g[i]; }
+        Vec16<T> w;
+        w.pack(o);
+        w.store_once(dyp + (long)rows[j] * d + c * N);
+      }
+      const float v = wave_sum(dot);
+      if (lane == 0) part[j][wv] = v;
+    }
+  }
+  __syncthreads();
+  if (tid < k) dgate[t * k + tid] = (part[tid][0] + part[tid][1]) + (part[tid][2] + part[tid][3]);   // fixed order
+}
+
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int n_partial, long n,
                                                               float* __restrict__ out, int accumulate) {
   const long i = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
@@ -178,6 +246,26 @@ void combine_dispatch(const void* yp, const int* inv, const float* gate, void* y
 int launch_combine(int dtype, const void* yp, const int* inv, const float* gate, void* y, int T, int d, int k, hipStream_t s) {
   if (dtype == SPES_F32) combine_dispatch<float>(yp, inv, gate, y, T, d, k, s);
   else combine_dispatch<bf16_t>(yp, inv, gate, y, T, d, k, s);
+  return ok();
+}
+
+template <typename T>
+void grad_scatter_dispatch(const void* dy, const void* yp, const int* inv, const float* gate, void* dyp, float* dgate, int Tn,
+                           int d, int k, hipStream_t s) {
+#define SPES_SCATTER(KU) \
+  hipLaunchKernelGGL((grad_scatter_kernel<T, KU>), dim3(Tn), dim3(256), 0, s, (const T*)dy, (const T*)yp, inv, gate, (T*)dyp, dgate, d, k)
+  if (k == 8) SPES_SCATTER(8);
+  else if (k == 4) SPES_SCATTER(4);
+  else if (k == 2) SPES_SCATTER(2);
+  else if (k == 1) SPES_SCATTER(1);
+  else SPES_SCATTER(0);
+#undef SPES_SCATTER
+}
+
+int launch_grad_scatter(int dtype, const void* dy, const void* yp, const int* inv, const float* gate, void* dyp, float* dgate,
+                        int T, int d, int k, hipStream_t s) {
+  if (dtype == SPES_F32) grad_scatter_dispatch<float>(dy, yp, inv, gate, dyp, dgate, T, d, k, s);
+  else grad_scatter_dispatch<bf16_t>(dy, yp, inv, gate, dyp, dgate, T, d, k, s);
   return ok();
 }
 

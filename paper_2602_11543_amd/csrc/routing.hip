@@ -199,9 +199,21 @@ __global__ __launch_bounds__(256) void gating_bwd_kernel(const float* __restrict
   float out = 0.f;
   const float lse_t = lse[t];
   const float p = (lane < M) ? expf(logits[(long)t * M + lane] - lse_t) : 0.f;
+  // Every term below has the shape v_e * (u_e - sum_j u_j v_j) with sum_j v_j = 1.  When routing collapses onto one
+  // expert (v -> 1 for the top score) that difference cancels completely in fp32 although the true value is about
+  // u * (1 - v).  Only the top entry can come close to 1, so it alone is written as
+  // v_m * (u_m * sum_{j != m} v_j - sum_{j != m} u_j v_j), which subtracts nothing large; selection is in descending
+  // score order, so the top expert is the one of slot 0.
+  const int top = __builtin_amdgcn_readlane(sel, 0);
+  const float pz = (lane == top) ? 0.f : p;
+  const float p_others = wave_sum(pz);
+  const float p_top = lane_value(p, top);
   if (renorm) {
-    const float dot = wave_sum(g * dg);
-    const float mine = g * (dg - dot);
+    const float gz = (lane == 0) ? 0.f : g;                  // lanes beyond k hold zero gates
+    const float g_others = wave_sum(gz);
+    const float dot_others = wave_sum(gz * dg);
+    const float g0 = lane_value(g, 0), dg0 = lane_value(dg, 0);
+    const float mine = (lane == 0) ? g0 * (dg0 * g_others - dot_others) : g * (dg - (dot_others + g0 * dg0));
     // scatter lane j's value to lane sel
     for (int j = 0; j < k; ++j) {
       const int ej = __builtin_amdgcn_readlane(sel, j);     // j is the same for the whole wavefront: scalar reads
@@ -215,15 +227,18 @@ __global__ __launch_bounds__(256) void gating_bwd_kernel(const float* __restrict
       const float vj = lane_value(dg, j);
       if (lane == ej) dp = vj;
     }
-    const float dot = wave_sum(dp * p);
-    out = p * (dp - dot);
+    const float dot_others = wave_sum(dp * pz);
+    const float dp_top = lane_value(dp, top);
+    out = (lane == top) ? p_top * (dp_top * p_others - dot_others) : p * (dp - (dot_others + dp_top * p_top));
   }
   // auxiliary router losses: aux[e] = dL/dp_e of the load-balancing term (the same for every token),
   // aux[kMaxExperts] = the z-loss factor 2 z / T; both are zero unless armed after the forward pass
   {
     const float c = (lane < M) ? aux[lane] : 0.f;
-    const float cp = wave_sum(c * p);
-    out += p * (c - cp) + aux[kMaxExperts] * lse_t * p;
+    const float c_others = wave_sum(c * pz);
+    const float c_top = lane_value(c, top);
+    const float lb = (lane == top) ? p_top * (c_top * p_others - c_others) : p * (c - (c_others + c_top * p_top));
+    out += lb + aux[kMaxExperts] * lse_t * p;
   }
   if (lane < M) {
     dlogits[(long)t * M + lane] = out;

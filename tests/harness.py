@@ -5,6 +5,7 @@ import numpy as np
 import torch
 
 import paper_2602_11543_amd as S
+from paper_2602_11543_amd.layer import DeviceLayer, shape_of, to_dev  # noqa: F401
 
 TOL = {"f32": 1e-5, "bf16": 2e-2}     # max |a-b| / max |b| per tensor (stated by the benchmark definition)
 
@@ -15,73 +16,26 @@ def rel_err(got, want) -> float:
     return float(np.abs(got - want).max() / (den if den > 0 else 1.0))
 
 
-def to_dev(a: np.ndarray, dtype: str, device) -> torch.Tensor:
-    t = torch.from_numpy(np.ascontiguousarray(a))
-    if dtype == "bf16":
-        t = t.to(torch.bfloat16)          # exact: the generator already rounded to bf16
-    return t.to(device)
+def storage_ulp_excess(got, want, mag, dtype, f32_ulps=2.0):
+    """How far `got` (values of the storage type) is from the fp64 result `want`, as the largest element-wise excess
+    over the allowance (<= 0: within it).  The device forms such results in fp32 from operands of magnitude up to
+    `mag` and rounds once: fp32 storage may differ by `f32_ulps` fp32 ulps at the magnitude of the operands (a mean
+    of nearly cancelling copies is tiny against them), bf16 storage by one bf16 ulp from the rounded fp64 value --
+    or by that same fp32 allowance where the result is so small that a bf16 ulp is below it."""
+    got64, want = np.asarray(got, dtype=np.float64), np.asarray(want, dtype=np.float64)
+    allow32 = f32_ulps * np.spacing(np.asarray(mag, dtype=np.float32)).astype(np.float64)
+    err = np.abs(got64 - want)
+    if dtype == "f32":
+        return float((err - allow32).max())
+    from spes_workloads import bf16_round
 
+    def ordered(a):        # bf16 values as integers that count representable steps, monotone through zero
+        b = np.asarray(a, dtype=np.float32).view(np.int32).astype(np.int64) >> 16
+        return np.where(b < 0, -(b & 0x7FFF), b)
 
-def shape_of(cfg) -> "S.spes_moe_shape":
-    return S.moe_shape(cfg.T, cfg.d, cfg.M, cfg.f, cfg.k, S.SPES_F32 if cfg.dtype == "f32" else S.SPES_BF16, cfg.renorm)
-
-
-class DeviceLayer:
-    """Device copies of one layer's inputs plus the output/ctx buffers of fwd and bwd."""
-
-    def __init__(self, inp: dict, device, mask=None):
-        cfg = inp["cfg"]
-        self.cfg, self.shape, self.dev = cfg, shape_of(cfg), device
-        dt = cfg.dtype
-        self.x = to_dev(inp["x"], dt, device); self.dy = to_dev(inp["dy"], dt, device)
-        self.w_router = to_dev(inp["w_router"], dt, device)
-        self.bias = None if inp["router_bias"] is None else torch.from_numpy(inp["router_bias"]).to(device)
-        self.w_gate = to_dev(inp["w_gate"], dt, device); self.w_up = to_dev(inp["w_up"], dt, device)
-        self.w_down = to_dev(inp["w_down"], dt, device)
-        st = S.torch_dtype(self.shape.dtype)
-        T, d, M, f, k = cfg.T, cfg.d, cfg.M, cfg.f, cfg.k
-        self.y = torch.empty(T, d, dtype=st, device=device)
-        self.idx = torch.empty(T, k, dtype=torch.int32, device=device)
-        self.gate = torch.empty(T, k, dtype=torch.float32, device=device)
-        self.count = torch.empty(M, dtype=torch.int32, device=device)
-        self.ctx = torch.empty(S.spes_moe_ctx_bytes(self.shape), dtype=torch.uint8, device=device)
-        self.dx = torch.empty(T, d, dtype=st, device=device)
-        self.d_w_router = torch.zeros(M, d, dtype=torch.float32, device=device)
-        self.set_mask(inp["trainable_mask"] if mask is None else mask)
-
-    def set_mask(self, mask):
-        cfg = self.cfg
-        self.mask = np.asarray(mask, dtype=np.uint8)
-        n = int(self.mask.sum())
-        self.trainable = [int(e) for e in np.nonzero(self.mask)[0]]
-        mk = lambda *s: torch.zeros(*s, dtype=torch.float32, device=self.dev) if n else None
-        self.d_w_gate, self.d_w_up, self.d_w_down = mk(n, cfg.f, cfg.d), mk(n, cfg.f, cfg.d), mk(n, cfg.d, cfg.f)
-
-    def fwd(self):
-        S.spes_moe_fwd(self.shape, self.x, self.w_router, self.bias, self.w_gate, self.w_up, self.w_down, self.y, self.idx,
-                       self.gate, self.count, self.ctx)
-
-    def bwd(self, accumulate=0):
-        S.spes_moe_bwd(self.shape, self.dy, self.x, self.w_router, self.w_gate, self.w_up, self.w_down, self.ctx, self.mask,
-                       self.dx, self.d_w_router, self.d_w_gate, self.d_w_up, self.d_w_down, accumulate)
-
-    def aux(self, lb_coef, z_coef, grad_scale=1.0):
-        """Router auxiliary losses of the last forward; arms the next bwd.  Returns (L_lb, L_z)."""
-        losses = torch.zeros(2, dtype=torch.float32, device=self.dev)
-        S.spes_moe_router_aux(self.shape, self.ctx, lb_coef, z_coef, grad_scale, losses)
-        return tuple(float(v) for v in losses.cpu().numpy())
-
-    def permuted(self):
-        """The dispatched copy of x in expert-contiguous order, from the routing tables of the last forward."""
-        xp = torch.empty(self.cfg.T * self.cfg.k, self.cfg.d, dtype=self.x.dtype, device=self.dev)
-        S.spes_moe_permute(self.shape, self.x, self.ctx, xp)
-        return xp
-
-    def view(self, name):
-        return S.ctx_view(self.shape, self.ctx, name)
-
-    def host(self, t):
-        return t.float().cpu().numpy() if t.dtype == torch.bfloat16 else t.cpu().numpy()
+    steps = np.abs(ordered(got) - ordered(bf16_round(want.astype(np.float32))))
+    bad = (steps > 1) & (err > 2 * allow32)
+    return float(np.where(bad, steps, 0).max())
 
 
 def oracle_run(inp, O, keep=True):

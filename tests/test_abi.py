@@ -9,8 +9,10 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_header_symbols_are_exported():
-    header = open(os.path.join(ROOT, "include", "spes.h")).read()
+    inc = os.path.join(ROOT, "include")
+    header = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
     names = set(re.findall(r"SPES_API[^;(]*?\b(spes_\w+)\s*\(", header))
+    assert {"spes_moe_grad_scatter", "spes_profile_enable", "spes_ref_mfma_rate"} <= names
     assert {"spes_moe_fwd", "spes_moe_bwd", "spes_expert_merge", "spes_expert_warmup_merge"} <= names
     lib = ctypes.CDLL(S.library_path())
     for n in names:

@@ -45,6 +45,11 @@ def test_layer_parity(name, device):
     dict(T=130, d=64, M=6, f=56, k=6, n_trainable=3),                   # k = M: dense mixture
     dict(T=257, d=136, M=64, f=72, k=3, n_trainable=7, trainable="random"),   # more experts than most tiles have rows
     dict(T=200, d=64, M=8, f=64, k=1, bias="normal", bias_scale=8.0),    # nearly every token to one expert, several empty
+    # collapsed routing: the top probability is 1 to within fp32 rounding, and the router gradient (about 1e-8 of the
+    # gate gradient) survives only because the gating backward never forms 1 - p by subtraction
+    dict(T=200, d=64, M=8, f=64, k=1, bias="normal", bias_scale=30.0),
+    dict(T=200, d=64, M=8, f=64, k=2, bias="normal", bias_scale=30.0),
+    dict(T=200, d=64, M=8, f=64, k=2, renorm=1, bias="normal", bias_scale=30.0),
     dict(T=333, d=264, M=16, f=200, k=4, renorm=1, dtype="bf16", n_trainable=5, trainable="random", router_sigma=0.05),
     dict(T=96, d=64, M=8, f=64, k=2, n_trainable=0),                    # nothing trainable: no weight-grad buffers at all
     # the same corners through the matrix-core path (bf16): contraction lengths of one and two K-tiles with and
@@ -54,6 +59,7 @@ def test_layer_parity(name, device):
     dict(T=130, d=64, M=6, f=56, k=6, n_trainable=3, dtype="bf16"),
     dict(T=257, d=136, M=64, f=72, k=3, n_trainable=7, trainable="random", dtype="bf16"),
     dict(T=200, d=128, M=8, f=128, k=1, bias="normal", bias_scale=8.0, dtype="bf16"),
+    dict(T=200, d=128, M=8, f=128, k=2, bias="normal", bias_scale=30.0, dtype="bf16"),
     dict(T=96, d=8, M=8, f=8, k=2, n_trainable=8, dtype="bf16"),        # the smallest feature sizes the library takes
     dict(T=300, d=192, M=12, f=320, k=2, renorm=1, n_trainable=0, dtype="bf16"),
     # outputs wide enough for the grouped tile order (at least 12 column tiles), with a ragged last group of row tiles

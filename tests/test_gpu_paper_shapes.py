@@ -20,7 +20,7 @@ def test_paper_shape_sampled(name, device):
     inp = layer_inputs(cfg)
     L = DeviceLayer(inp, device)
     L.fwd(); L.bwd(); torch.cuda.synchronize()
-    _check_sampled(L, inp, _routing_all_tokens(inp), n_tokens=512, n_experts=1)
+    _check_sampled(L, inp, _routing_all_tokens(inp), n_tokens=512)
 
 
 def test_two_micro_batches_accumulate(device):
