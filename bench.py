@@ -318,7 +318,7 @@ def layer_figures(cfg_name: str, args, full: bool) -> dict:
         L.fwd()
         L.bwd(0)
 
-    copy_gbs = None
+    copy_gbs = fill_gbs = None
     if full:
         # a plain 1 GiB device copy: reference point for the HBM byte counters and for what a stream achieves here
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
@@ -332,6 +332,13 @@ def layer_figures(cfg_name: str, args, full: bool) -> dict:
         e1.record()
         torch.cuda.synchronize()
         copy_gbs = 3 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        # a pure write stream (the dispatch copy is eight ninths writes at top-8)
+        e0.record()
+        for _ in range(3):
+            dst.fill_(7)
+        e1.record()
+        torch.cuda.synchronize()
+        fill_gbs = 3 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
         del src, dst
 
     run = step
@@ -443,9 +450,11 @@ def layer_figures(cfg_name: str, args, full: bool) -> dict:
     if copy_gbs is not None:
         out["hbm_copy_reference"] = {"achieved": round(copy_gbs, 1), "unit": "GB/s", "frac": round(copy_gbs / PEAK_HBM_GBS, 4),
                                      "what": "plain 1 GiB device-to-device copy (read + write bytes) on this GPU"}
+        out["hbm_fill_reference"] = {"achieved": round(fill_gbs, 1), "unit": "GB/s", "frac": round(fill_gbs / PEAK_HBM_GBS, 4),
+                                     "what": "plain 1 GiB device fill (write bytes only) on this GPU"}
     if mfma_tflops is not None:
         out["mfma_reference"] = {"achieved": round(mfma_tflops, 1), "unit": "TFLOP/s", "frac_of_nominal": round(mfma_tflops / PEAK_BF16_TFLOPS, 4),
-                                 "what": "register-resident 32x32x16 bf16 MFMA loop on this GPU, operands taken from the workload's expert "
+                                 "what": "register-resident 16x16x32 bf16 MFMA loop on this GPU, operands taken from the workload's expert "
                                          "weights: the power-limited matrix rate on data like the workload's"}
         out["grouped_gemm_util"]["frac_of_mfma_reference"] = round(gemm_flop / (gemm_ms * 1e-3) / 1e12 / mfma_tflops, 4)
     tr = profiled_traffic(cfg.name, dominant)

@@ -15,7 +15,7 @@ extern "C" {
 #endif
 
 /* Reference rate of the matrix cores, for benchmarks: launches `blocks` workgroups of four
- * wavefronts that each run `iters` rounds of sixteen 32x32x16 bf16 MFMAs on operands held in
+ * wavefronts that each run `iters` rounds of sixty-four 16x16x32 bf16 MFMAs on operands held in
  * registers, taken from `data`.  The shader clock under matrix load depends on the operand
  * values (power), so the rate to compare a GEMM with is this loop timed on values like the
  * GEMM's.  The caller times the launch (events on `stream`); *flop receives the number of

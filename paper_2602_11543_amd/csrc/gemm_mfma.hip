@@ -1,7 +1,11 @@
-// Grouped bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate).
+// Grouped bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_16x16x32_bf16, fp32 accumulate).
 //
 // A 256-thread block (four wavefronts, 2 x 2) computes a BM x BN output tile, each
-// wavefront a (BM/2) x (BN/2) sub-tile as TM x TN MFMA tiles of 32 x 32 held in AGPRs.
+// wavefront a (BM/2) x (BN/2) sub-tile as TM x TN MFMA tiles of 16 x 16 held in AGPRs.
+// The 16x16x32 form of the instruction is used because it is the cheaper one in power, and
+// power is what bounds these kernels: on the same operand values a register-resident loop of it
+// sustains about 2.1 PFLOP/s at 2.1 GHz where the 32x32x16 form sustains 1.85 PFLOP/s at
+// 1.83 GHz (it moves half as many accumulator registers per multiply-add).
 // Operand tiles are staged global -> registers -> LDS with two LDS stages:
 //   * a register is written to LDS (K-tile t+1) and at once reloaded from global
 //     memory (K-tile t+2), so every load has a whole iteration to land;
@@ -12,8 +16,9 @@
 //     issued before the MFMAs of k-step s, and the first fragments of the next K-tile
 //     are read (after the block barrier) under the last MFMAs of the current one.
 // An operand whose contraction index is the fast memory axis lives in LDS as [row][k]
-// with a row pitch of BK*2+16 bytes, which spreads the fragment reads (16 rows x one
-// 16-byte chunk) over all banks.
+// without padding; the 16-byte chunks of a row are permuted by the row number (kc_unit)
+// so that both the fragment reads (16 rows x one chunk) and the staging writes (2 rows x
+// 8 chunks) of a group of sixteen lanes cover all banks.
 // An operand whose contraction index is the slow memory axis (the weights in the
 // input-gradient GEMMs, both operands of the weight-gradient GEMMs) keeps its memory
 // order in LDS, [k][row] with a pitch of rows*2+64 bytes: it is loaded in 512-byte
@@ -40,17 +45,19 @@ namespace spes {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 constexpr int kXcds = 8;
 
 template <int BM_, int BN_, int BK_, int MINB_>
 struct Cfg {
   static constexpr int BM = BM_, BN = BN_, BK = BK_, MINB = MINB_;
-  static constexpr int TM = BM / 64, TN = BN / 64;          // MFMA tiles per wavefront along m, n
-  static constexpr int KSTEPS = BK / 16;
+  static constexpr int TM = BM / 32, TN = BN / 32;          // 16 x 16 MFMA tiles per wavefront along m, n
+  static constexpr int TS = BM / 64;                        // 32-row slabs of a wavefront's sub-tile (epilogues)
+  static constexpr int KSTEPS = BK / 32;                    // one MFMA contracts 32 k
   static constexpr int CH = BK / 8;                         // 16-byte chunks of data per LDS row
-  static constexpr int PITCH = CH + 1;                      // row pitch in 16-byte units
+  static constexpr int PITCH = CH;                          // row pitch in 16-byte units: no padding, the chunks of a row are
+                                                            // permuted instead (kc_unit below)
   static constexpr int RP = 256 / CH;                       // rows staged per pass (K-contiguous operand)
   static constexpr int NA = BM / RP, NB = BN / RP;          // staging registers (uint4) per thread, K-contiguous
   static constexpr int KPA_ = BM / 8 + 4, KPB_ = BN / 8 + 4;
@@ -67,6 +74,13 @@ struct Cfg {
   static constexpr int RB = NB > NBS ? NB : NBS;
   static_assert(BK * KPA <= A_VEC && BK * KPB <= B_VEC, "the [k][row] layout must fit the operand's LDS region");
 };
+
+// Position (in 16-byte units) of chunk c of row `row` in the [row][k] LDS layout of a K-contiguous operand with CH
+// chunks per row: the chunk index is XORed with bits 1.. of the row.  Sixteen units span all 64 banks; the unit of
+// (row, c) modulo 16 is (row & 1) * 8 + (c ^ (row >> 1) & 7), so the sixteen rows one group of lanes reads at a
+// common chunk (a fragment read), and the two rows times eight chunks one group of lanes writes, each cover all banks.
+template <int CH>
+__device__ __forceinline__ int kc_unit(int row, int c) { return row * CH + (c ^ ((row >> 1) & (CH - 1))); }
 
 __device__ __forceinline__ uint4 zero4() { return make_uint4(0, 0, 0, 0); }
 // branch-free: the main loop must stay one basic block so that the compiler counts outstanding loads exactly
@@ -101,7 +115,7 @@ __device__ __forceinline__ uint2 lds_read_tr(const bf16_t* p) {
 }
 
 constexpr int kGroupRows = 4;      // row tiles per group of the tile order (ragged-row GEMMs) ...
-constexpr int kGroupMinCols = 12;  // ... used when the output has at least this many column tiles
+constexpr int kGroupMinCols = 8;   // ... used when the output has at least this many column tiles
 
 // A_KG / B_KG: the K-strided operand A / B takes its k-rows through the index table a_rows / b_rows (the dy rows,
 // or the input rows, of an expert's routed pairs)
@@ -110,7 +124,7 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   constexpr int BM = C::BM, BN = C::BN, BK = C::BK, TM = C::TM, TN = C::TN, CH = C::CH, RP = C::RP;
   __shared__ uint4 smem[2 * C::STAGE_VEC];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int l32 = lane & 31, lhalf = lane >> 5;
+  const int l16 = lane & 15, lq = lane >> 4;          // an MFMA operand: lane holds row l16, k = lq*8 .. lq*8+7 of a 32-wide k-step
   const int wm = wave >> 1, wn = wave & 1;
   constexpr int BNO = (EPI == kEpiSwiglu) ? BN / 2 : BN;   // output columns per tile
 
@@ -215,13 +229,14 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
     }
   }
 
-  f32x16 acc[TN][TM];
+  // acc[j][i][r] = C(m = i*16 + l16, n = j*16 + lq*4 + r) of the wavefront's sub-tile
+  f32x4 acc[TN][TM];
 #pragma unroll
   for (int j = 0; j < TN; ++j)
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
+      for (int r = 0; r < 4; ++r) acc[j][i][r] = 0.f;
 
   const int npass = (EPI == kEpiSwiglu) ? 1 : g.npairs;
   const long klen = k_end - k_begin;
@@ -320,7 +335,7 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   auto write_a = [&](int stage, int idx, bool masked) {
     uint4* ta = smem + stage * C::STAGE_VEC;
     if (A_KC) {
-      ta[(tid / CH + RP * idx) * C::PITCH + tid % CH] = masked ? sel4(a_keep != 0, ra[idx]) : copy4(ra[idx]);
+      ta[kc_unit<CH>(tid / CH + RP * idx, tid % CH)] = masked ? sel4(a_keep != 0, ra[idx]) : copy4(ra[idx]);
     } else {
       ta[(tid / ACH + idx * C::KRA) * C::KPA + tid % ACH] = masked ? sel4((a_keep >> idx) & 1u, ra[idx]) : copy4(ra[idx]);
     }
@@ -328,7 +343,7 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   auto write_b = [&](int stage, int idx, bool masked) {
     uint4* tb = smem + stage * C::STAGE_VEC + C::A_VEC;
     if (B_KC) {
-      tb[(tid / CH + RP * idx) * C::PITCH + tid % CH] = masked ? sel4(b_keep != 0, rb[idx]) : copy4(rb[idx]);
+      tb[kc_unit<CH>(tid / CH + RP * idx, tid % CH)] = masked ? sel4(b_keep != 0, rb[idx]) : copy4(rb[idx]);
     } else {
       tb[(tid / BCH + idx * C::KRB) * C::KPB + tid % BCH] = masked ? sel4((b_keep >> idx) & 1u, rb[idx]) : copy4(rb[idx]);
     }
@@ -345,14 +360,14 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   };
 
   bf16x8 fa[2][TM], fb[2][TN];
-  const int tr_k = lhalf * 8 + (lane & 15) / 4;                  // k-row (within a k-step) this lane points the transposing read at
-  const int tr_r = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;      // row (within a 32-row MFMA tile) likewise
+  const int tr_k = lq * 8 + (lane & 15) / 4;                     // k-row (within a k-step) this lane points the transposing read at
+  const int tr_r = (lane & 3) * 4;                               // row (within a 16-row MFMA tile) likewise
   auto read_frag_a = [&](int stage, int ks, int set, int i) {
     const uint4* ta = smem + stage * C::STAGE_VEC;
     if (A_KC) {
-      fa[set][i] = __builtin_bit_cast(bf16x8, ta[(wm * (BM / 2) + i * 32 + l32) * C::PITCH + ks * 2 + lhalf]);
+      fa[set][i] = __builtin_bit_cast(bf16x8, ta[kc_unit<CH>(wm * (BM / 2) + i * 16 + l16, ks * 4 + lq)]);
     } else {
-      const bf16_t* p = reinterpret_cast<const bf16_t*>(ta + (ks * 16 + tr_k) * C::KPA) + wm * (BM / 2) + i * 32 + tr_r;
+      const bf16_t* p = reinterpret_cast<const bf16_t*>(ta + (ks * 32 + tr_k) * C::KPA) + wm * (BM / 2) + i * 16 + tr_r;
       const uint2 lo = lds_read_tr(p), hi = lds_read_tr(p + 4 * C::KPA * 8);
       fa[set][i] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
     }
@@ -360,9 +375,9 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   auto read_frag_b = [&](int stage, int ks, int set, int j) {
     const uint4* tb = smem + stage * C::STAGE_VEC + C::A_VEC;
     if (B_KC) {
-      fb[set][j] = __builtin_bit_cast(bf16x8, tb[(wn * (BN / 2) + j * 32 + l32) * C::PITCH + ks * 2 + lhalf]);
+      fb[set][j] = __builtin_bit_cast(bf16x8, tb[kc_unit<CH>(wn * (BN / 2) + j * 16 + l16, ks * 4 + lq)]);
     } else {
-      const bf16_t* p = reinterpret_cast<const bf16_t*>(tb + (ks * 16 + tr_k) * C::KPB) + wn * (BN / 2) + j * 32 + tr_r;
+      const bf16_t* p = reinterpret_cast<const bf16_t*>(tb + (ks * 32 + tr_k) * C::KPB) + wn * (BN / 2) + j * 16 + tr_r;
       const uint2 lo = lds_read_tr(p), hi = lds_read_tr(p + 4 * C::KPB * 8);
       fb[set][j] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
     }
@@ -394,43 +409,48 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
     read_frags(0, 0, 0);
 
     constexpr int MF = TM * TN;                       // MFMAs per k-step
-    constexpr int SLOTS = (C::KSTEPS - 1) * MF;       // MFMA slots before the barrier of an iteration
+    constexpr int NF = TM + TN;                       // fragments per k-step
+    static_assert(C::KSTEPS == 2 && NP == NF, "the schedule below deals one staging register per fragment over a K-tile of two k-steps");
+    constexpr int FR = MF / NF;                       // MFMA gaps per fragment in the first k-step
+    constexpr int R1 = FR > 1 ? 1 : 0, R2 = FR > 2 ? 2 : FR - 1;
+    constexpr int QB = MF - 2 * NF >= 0 ? MF / 4 : 0; // the barrier sits before this MFMA of the second k-step ...
+    constexpr int RT = (MF - QB) / NF;                // ... and the next K-tile's fragments follow it, one every RT gaps
+    static_assert(FR >= 1 && RT >= 1, "more fragments than MFMA gaps");
     // One iteration: MFMAs of K-tile t from LDS stage t&1, K-tile t+1 from registers to the other stage, K-tile t+2
     // from memory to registers.  No branches in here: past the last K-tile the pipeline keeps running on clamped
     // tiles whose results are never used (a spare LDS write, a repeated load).
+    // Everything besides the MFMAs is dealt out over the gaps between them, at most one memory instruction per gap
+    // where the tile is large enough.  First k-step, gaps w*FR .. w*FR+2: fragment w of the second k-step, the LDS
+    // write of staging register w (K-tile t+1), its reload (K-tile t+2).  Second k-step: the block barrier that
+    // publishes K-tile t+1, then the fragments of its first k-step.
     auto iteration = [&](int t, auto masked_c) __attribute__((always_inline)) {
       constexpr bool MASKED = decltype(masked_c)::value;
       const int cur = t & 1;
       set_load_tile(t + 2 < nsteps ? t + 2 : nsteps - 1);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int ks = 0; ks < C::KSTEPS; ++ks) {
-        const int set = ks & 1;
-        // next k-step's stage: after the last k-step comes the next K-tile, published by the barrier below
-        const int nstage = (ks + 1 < C::KSTEPS) ? cur : cur ^ 1, nks = (ks + 1 < C::KSTEPS) ? ks + 1 : 0;
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int q = 0; q < MF; ++q) {
-          const int j = q / TM, i = q % TM;
-          acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[j][i], 0, 0, 0);
-          // everything else is dealt out over the gaps between MFMAs in portions that fit under one MFMA:
-          // one fragment read of the next k-step every FR-th gap, and per staging register its LDS write in
-          // one gap and its reload in the next
-          constexpr int FR = MF / (TM + TN) > 0 ? MF / (TM + TN) : 1;
-          if (q % FR == 0 && q / FR < TM + TN) read_frag(nstage, nks, set ^ 1, q / FR);
-          if (ks < C::KSTEPS - 1) {
-            const int slot = ks * MF + q;
-#pragma unroll
-            for (int p = 0; p < NP; ++p) {
-              if (p * SLOTS / NP == slot) piece(p, cur ^ 1, true, false, MASKED);
-              if (p * SLOTS / NP + 1 == slot) piece(p, cur ^ 1, false, true, MASKED);
-            }
-          }
-          __builtin_amdgcn_sched_barrier(0);
+      for (int q = 0; q < MF; ++q) {
+        const int j = q / TM, i = q % TM;
+        acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[0][j], fa[0][i], acc[j][i], 0, 0, 0);
+        const int w = q / FR, r = q % FR;
+        if (w < NF) {
+          if (r == 0) read_frag(cur, 1, 1, w);
+          if (r == R1) piece(w, cur ^ 1, true, false, MASKED);
+          if (r == R2) piece(w, cur ^ 1, false, true, MASKED);
         }
-        if (ks == C::KSTEPS - 2) {
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int q = 0; q < MF; ++q) {
+        const int j = q / TM, i = q % TM;
+        if (q == QB) {
           a_keep = a_keep_n; b_keep = b_keep_n;
           __syncthreads();
+          __builtin_amdgcn_sched_barrier(0);
         }
+        acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[1][j], fa[1][i], acc[j][i], 0, 0, 0);
+        if (q >= QB && (q - QB) % RT == 0 && (q - QB) / RT < NF) read_frag(cur ^ 1, 0, 0, (q - QB) / RT);
+        __builtin_amdgcn_sched_barrier(0);
       }
     };
     // The body exists twice: an inner loop without the k-tail selects for the tiles in the middle of a pass, and one
@@ -452,7 +472,8 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   // pieces over 32 rows per store.  Each wavefront therefore turns its sub-tile through a private LDS region,
   // 32 rows at a time, and comes back with lanes laid along the columns: every global access below is a run of
   // 256 to 512 contiguous bytes per row.
-  constexpr int ECOLS = TN * 32, EPITCH = ECOLS + 4; // floats per LDS row (pitch keeps the writes conflict-free)
+  constexpr int ECOLS = TN * 16, EPITCH = ECOLS + 4; // floats per LDS row
+  constexpr int TS = C::TS;                          // 32-row slabs: slab i holds the MFMA row tiles 2i and 2i+1
   float* ep = reinterpret_cast<float*>(smem) + wave * (32 * EPITCH);
   // output addresses are a per-tile base (uniform) plus a 32-bit element offset: row within the tile times the row
   // stride plus the column; rows are compared with the tile's valid row count in 32 bits as well
@@ -492,7 +513,7 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
   load_ab(0, 0);
   __syncthreads();                                   // the staging tiles are dead from here on
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
+  for (int i = 0; i < TS; ++i) {
     if (EPI == kEpiStore && !g.c_f32) {
       // bf16 output: round first, so that half as many bytes make the trip through LDS; rows of ECOLS bf16 with a
       // pitch of ECOLS*2+8 bytes (the 32 rows one write instruction touches fall into different banks)
@@ -501,9 +522,9 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int gq = 0; gq < 4; ++gq)
-          *reinterpret_cast<uint2*>(eb + l32 * BPITCH + (j * 32 + gq * 8 + lhalf * 4) * 2) =
-              make_uint2(pack2(acc[j][i][gq * 4], acc[j][i][gq * 4 + 1]), pack2(acc[j][i][gq * 4 + 2], acc[j][i][gq * 4 + 3]));
+        for (int ii = 0; ii < 2; ++ii)
+          *reinterpret_cast<uint2*>(eb + (ii * 16 + l16) * BPITCH + (j * 16 + lq * 4) * 2) =
+              make_uint2(pack2(acc[j][2 * i + ii][0], acc[j][2 * i + ii][1]), pack2(acc[j][2 * i + ii][2], acc[j][2 * i + ii][3]));
       constexpr int CPR = ECOLS / 8, RPI = 64 / CPR;   // lanes per row (eight columns each), rows per access
       const int c8 = lane % CPR;
       const long n = n0 + wn * (BN / 2) + c8 * 8;
@@ -523,15 +544,16 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int gq = 0; gq < 4; ++gq) {
-        // the dSwiGLU epilogue reads two adjacent 4-column groups per lane: even groups are kept in the first half
-        // of the LDS row and odd groups in the second, so that each of its reads is contiguous across the lanes
-        // (the SwiGLU epilogue does the same inside the gate half and inside the up half of its row)
-        const int col = (EPI == kEpiDSwiglu) ? lhalf * (ECOLS / 2) + (j * 4 + gq) * 4
-                      : (EPI == kEpiSwiglu)  ? (j / (TN / 2)) * (ECOLS / 2) + lhalf * (ECOLS / 4) + ((j % (TN / 2)) * 4 + gq) * 4
-                                             : j * 32 + gq * 8 + lhalf * 4;
-        *reinterpret_cast<float4*>(ep + l32 * EPITCH + col) =
-            make_float4(acc[j][i][gq * 4], acc[j][i][gq * 4 + 1], acc[j][i][gq * 4 + 2], acc[j][i][gq * 4 + 3]);
+      for (int ii = 0; ii < 2; ++ii) {
+        // The lane holds the 4-column group j*4 + lq of row ii*16 + l16.  The dSwiGLU epilogue reads two adjacent
+        // groups per lane: even groups are kept in the first half of the LDS row and odd groups in the second, so that
+        // each of its reads is contiguous across the lanes (the SwiGLU epilogue does the same inside the gate half
+        // and inside the up half of its row: tiles j < TN/2 are the gate columns, the others the up columns)
+        const int col = (EPI == kEpiDSwiglu) ? (lq & 1) * (ECOLS / 2) + (j * 2 + (lq >> 1)) * 4
+                      : (EPI == kEpiSwiglu)  ? (j / (TN / 2)) * (ECOLS / 2) + (lq & 1) * (ECOLS / 4) + ((j % (TN / 2)) * 2 + (lq >> 1)) * 4
+                                             : j * 16 + lq * 4;
+        *reinterpret_cast<float4*>(ep + (ii * 16 + l16) * EPITCH + col) =
+            make_float4(acc[j][2 * i + ii][0], acc[j][2 * i + ii][1], acc[j][2 * i + ii][2], acc[j][2 * i + ii][3]);
       }
     if (EPI == kEpiStore) {
       constexpr int CPR = ECOLS / 4, RPI = 64 / CPR;   // lanes per row, rows per access
@@ -556,7 +578,7 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
       // each with its even 4-column groups first and its odd ones behind.  A lane takes eight output columns of a row
       // (16-byte bf16 stores); the two rows that one 16-lane phase of a read touches are eight rows apart, which is 32
       // banks with this pitch.
-      static_assert(EPI != kEpiSwiglu || (TN == 4 && ECOLS == 128), "lane layout of the SwiGLU epilogue");
+      static_assert(EPI != kEpiSwiglu || (TN == 8 && ECOLS == 128), "lane layout of the SwiGLU epilogue");
       const int c8 = lane & 7, rsel = lane >> 3;
       const long n = n0 + wn * (BN / 4) + c8 * 8;
       const bool n_in = n < g.Ndim;
@@ -649,7 +671,7 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
         // be acknowledged, and every half-slab would pay a full load and a full store round trip in sequence.
         __builtin_amdgcn_sched_barrier(0);
         if (hf + 1 < DS_NB) load_ab(i, hf + 1);
-        else if (i + 1 < TM) load_ab(i + 1, 0);
+        else if (i + 1 < TS) load_ab(i + 1, 0);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int q = 0; q < DS_HALF; ++q) {

@@ -51,7 +51,7 @@ int launch_upcycle_init(int dtype, int n_experts, long elems, const void* dense,
 int launch_expert_pack(int dtype, int n_experts, long elems, void* store, const unsigned char* mask, void* packed, int to_store,
                        hipStream_t s);
 
-// reference.hip: register-resident MFMA loop (blocks x 4 wavefronts x iters x 16 MFMAs); *flop = operations launched
+// reference.hip: register-resident MFMA loop (blocks x 4 wavefronts x iters x 64 MFMAs of 16x16x32); *flop = operations launched
 int launch_mfma_rate(const void* data, int blocks, int iters, float* sink, double* flop, hipStream_t s);
 
 }  // namespace spes

@@ -77,29 +77,28 @@ __global__ void write_counts_kernel(const CountTable tb, int* __restrict__ train
 
 // Gram matrix of up to 64 bf16 rows, G = W W^T, as partial sums over chunks of the (long) row length: a pure stream of
 // the matrix, read once (Eq. 5: all pairwise inner products of the flattened input projections).
-// Both operands of every product are the same data, so nothing is staged: lane l of a wavefront loads the sixteen bytes
-// of row l%32 (+32 for the second fragment) that a 32x32x16 MFMA expects at k = (l/32)*8 .. +8 of a 16-wide k-step, and
-// the two fragments feed all four 32x32 blocks of the 64x64 result.  Register r of lane l of block (i,j) holds
-// G[32i + (r/4)*8 + (l/32)*4 + r%4][32j + l%32].  The four wavefronts of a block take a quarter of the block's chunk
-// each and are added in wavefront order through LDS; the block partials are added in block order by gram_reduce_kernel.
+// The rows lie a whole matrix row apart (megabytes, usually a power of two): an access that touches many rows at the
+// same column lands on one memory channel.  Every load instruction therefore reads 1 KB of a single row (64 lanes x
+// 16 bytes), and the 64 x 512 sub-tile goes through LDS (global -> registers -> LDS, the next sub-tile's loads in
+// flight while this one is multiplied).  Both operands of every product are the same data: lane l reads the sixteen
+// bytes of row l%32 (+32 for the second fragment) that a 32x32x16 MFMA expects at k = (l/32)*8 .. +8 of a k-step, and
+// the two fragments feed all four 32x32 blocks of the 64x64 result; register r of lane l of block (i,j) holds
+// G[32i + (r/4)*8 + (l/32)*4 + r%4][32j + l%32].  Wavefront w multiplies k-steps 8w .. 8w+7 of every sub-tile; the four
+// wavefronts are added in order through LDS, the block partials in block order by gram_reduce_kernel.
 typedef __attribute__((ext_vector_type(8))) __bf16 gram_bf16x8;
 typedef __attribute__((ext_vector_type(16))) float gram_f32x16;
-constexpr int kGramUnroll = 8;      // k-steps requested together: sixteen 16-byte loads per lane in flight
-constexpr int kGramPitch = 65;      // floats per LDS row (odd: the two row groups of a store fall into different banks)
+constexpr int kGramK = 512;                    // columns per sub-tile: 1 KB of every row
+constexpr int kGramPitch = kGramK / 8 + 1;     // LDS row pitch in 16-byte units (odd: fragment reads spread over the banks)
+constexpr int kGramRed = 65;                   // floats per row of the reduction buffer
 
 __global__ __launch_bounds__(256, 2) void gram_bf16_kernel(const bf16_t* __restrict__ w, int M, long elems, long kchunk,
                                                            float* __restrict__ partial) {
-  __shared__ float red[4][64 * kGramPitch];
+  __shared__ uint4 tile[64 * kGramPitch];
+  static_assert(sizeof(uint4) * 64 * kGramPitch >= sizeof(float) * 4 * 64 * kGramRed, "the reduction reuses the tile");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int row = lane & 31, half = lane >> 5;
   const long c0 = (long)blockIdx.x * kchunk;
   const long c1 = c0 + kchunk < elems ? c0 + kchunk : elems;
-  const long quarter = kchunk / 4;                       // a multiple of 16: k-steps never straddle two wavefronts
-  const long k0 = c0 + wave * quarter;
-  const long k1 = k0 + quarter < c1 ? k0 + quarter : c1;
-  const bool r0_in = row < M, r1_in = row + 32 < M;
-  const bf16_t* p0 = w + (long)(r0_in ? row : 0) * elems + half * 8;
-  const bf16_t* p1 = w + (long)(r1_in ? row + 32 : 0) * elems + half * 8;
   gram_f32x16 acc[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -107,56 +106,76 @@ __global__ __launch_bounds__(256, 2) void gram_bf16_kernel(const bf16_t* __restr
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-  for (long k = k0; k < k1; k += 16 * kGramUnroll) {
-    uint4 f0[kGramUnroll], f1[kGramUnroll];
+  // staging register i of this thread: 16 bytes at column 8*lane of row 4*i + wave
+  uint4 st[16];
+  auto load_tile = [&](long k) {
+    const long kk = k + lane * 8;                         // elems is a multiple of 8: a vector is inside or outside as a whole
 #pragma unroll
-    for (int u = 0; u < kGramUnroll; ++u) {
-      const long kk = k + u * 16 + half * 8;             // this lane's eight elements of k-step u (elems is a multiple of 8)
-      const bool in = kk < k1;
-      f0[u] = (in && r0_in) ? load_stream(reinterpret_cast<const uint4*>(p0 + k + u * 16)) : make_uint4(0, 0, 0, 0);
-      f1[u] = (in && r1_in) ? load_stream(reinterpret_cast<const uint4*>(p1 + k + u * 16)) : make_uint4(0, 0, 0, 0);
+    for (int i = 0; i < 16; ++i) {
+      const int r = 4 * i + wave;
+      st[i] = (r < M && kk < c1) ? load_stream(reinterpret_cast<const uint4*>(w + (long)r * elems + kk)) : make_uint4(0, 0, 0, 0);
     }
+  };
+  load_tile(c0);
+  for (long k = c0; k < c1; k += kGramK) {
+    __syncthreads();                                      // the previous sub-tile has been read by every wavefront
 #pragma unroll
-    for (int u = 0; u < kGramUnroll; ++u) {
-      const gram_bf16x8 a = __builtin_bit_cast(gram_bf16x8, f0[u]), b = __builtin_bit_cast(gram_bf16x8, f1[u]);
+    for (int i = 0; i < 16; ++i) tile[(4 * i + wave) * kGramPitch + lane] = st[i];
+    __syncthreads();
+    if (k + kGramK < c1) load_tile(k + kGramK);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int ks = wave * 8 + u;
+      const gram_bf16x8 a = __builtin_bit_cast(gram_bf16x8, tile[row * kGramPitch + ks * 2 + half]);
+      const gram_bf16x8 b = __builtin_bit_cast(gram_bf16x8, tile[(row + 32) * kGramPitch + ks * 2 + half]);
       acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, a, acc[0][0], 0, 0, 0);
       acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[0][1], 0, 0, 0);
       acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, acc[1][0], 0, 0, 0);
       acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, b, acc[1][1], 0, 0, 0);
     }
   }
+  __syncthreads();
+  float* red = reinterpret_cast<float*>(tile);
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r)
-        red[wave][(32 * i + (r / 4) * 8 + half * 4 + r % 4) * kGramPitch + 32 * j + row] = acc[i][j][r];
+        red[wave * 64 * kGramRed + (32 * i + (r / 4) * 8 + half * 4 + r % 4) * kGramRed + 32 * j + row] = acc[i][j][r];
   __syncthreads();
   float* out = partial + (long)blockIdx.x * M * M;
   for (int e = tid; e < M * M; e += 256) {
     const int i = e / M, j = e - i * M;
-    const int at = i * kGramPitch + j;
-    out[e] = ((red[0][at] + red[1][at]) + red[2][at]) + red[3][at];
+    const int at = i * kGramRed + j;
+    out[e] = ((red[at] + red[64 * kGramRed + at]) + red[2 * 64 * kGramRed + at]) + red[3 * 64 * kGramRed + at];
   }
 }
 
-// Sum the Gram partials in a fixed order: entry i of the result lands in partial 0.
-__global__ __launch_bounds__(64) void gram_reduce_kernel(float* __restrict__ partial, int n_partial, int n) {
-  const int i = blockIdx.x * 64 + threadIdx.x;
-  if (i >= n) return;
+// Sum the Gram partials in a fixed order: entry i of the result lands in partial 0.  Wavefront q of a block adds the
+// q-th quarter of the partials (ascending), the four quarter sums are then added in order.
+__global__ __launch_bounds__(256) void gram_reduce_kernel(float* __restrict__ partial, int n_partial, int n) {
+  __shared__ float quarter[4][64];
+  const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int i = blockIdx.x * 64 + lane;
+  const int per = (n_partial + 3) / 4;
+  const int p0 = q * per, p1 = p0 + per < n_partial ? p0 + per : n_partial;
   float acc = 0.f;
-  // sixteen loads in flight at a time; the additions keep the order p = 0, 1, 2, ...
-  int p = 0;
-  for (; p + 16 <= n_partial; p += 16) {
-    float v[16];
+  if (i < n) {
+    // sixteen loads in flight at a time; the additions keep the order p = p0, p0+1, ...
+    int p = p0;
+    for (; p + 16 <= p1; p += 16) {
+      float v[16];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) v[u] = partial[(long)(p + u) * n + i];
+      for (int u = 0; u < 16; ++u) v[u] = partial[(long)(p + u) * n + i];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) acc += v[u];
+      for (int u = 0; u < 16; ++u) acc += v[u];
+    }
+    for (; p < p1; ++p) acc += partial[(long)p * n + i];
   }
-  for (; p < n_partial; ++p) acc += partial[(long)p * n + i];
-  partial[i] = acc;
+  quarter[q][lane] = acc;
+  __syncthreads();                 // every partial of these 64 entries has been read before entry i of partial 0 is overwritten
+  if (q == 0 && i < n) partial[i] = ((quarter[0][lane] + quarter[1][lane]) + quarter[2][lane]) + quarter[3][lane];
 }
 
 // Normalise the Gram matrix to cosines and pick each row's top-K peers.  Eq. 5 is undefined for an expert whose
@@ -291,13 +310,13 @@ int launch_sync_merge(int dtype, int n_experts, long elems, int n_nodes, const v
 
 // partial[b][M*M], b < n_groups: Gram partial of columns [b*kchunk, (b+1)*kchunk) of the bf16 matrix w [M, elems]
 int launch_gram_bf16(const void* w, int M, long elems, int n_groups, long kchunk, float* partial, hipStream_t s) {
-  if (M > 64 || kchunk % 64 != 0 || elems % 8 != 0) return SPES_ESHAPE;
+  if (M > 64 || kchunk % 8 != 0 || elems % 8 != 0) return SPES_ESHAPE;
   hipLaunchKernelGGL(gram_bf16_kernel, dim3(n_groups), dim3(256), 0, s, (const bf16_t*)w, M, elems, kchunk, partial);
   return ok();
 }
 
 int launch_sim_topk(float* partial, int n_partial, int M, int K, float* sim, int* nbr, hipStream_t s) {
-  hipLaunchKernelGGL(gram_reduce_kernel, dim3(cdiv((long)M * M, 64)), dim3(64), 0, s, partial, n_partial, M * M);
+  hipLaunchKernelGGL(gram_reduce_kernel, dim3(cdiv((long)M * M, 64)), dim3(256), 0, s, partial, n_partial, M * M);
   hipLaunchKernelGGL(sim_topk_kernel, dim3(cdiv(M, 4)), dim3(256), 0, s, partial, M, K, sim, nbr);
   return ok();
 }

@@ -133,5 +133,5 @@ def test_mfma_reference_loop_runs_and_counts_its_work():
     sink = torch.full((8,), float("nan"), device=dev)
     flop = S.spes_ref_mfma_rate(data, 8, 10, sink)
     torch.cuda.synchronize()
-    assert flop == 8 * 4 * 10 * 16 * 2.0 * 32 * 32 * 16
+    assert flop == 8 * 4 * 10 * 64 * 2.0 * 16 * 16 * 32
     assert bool(torch.isfinite(sink).all())
