@@ -277,6 +277,22 @@ SPES_API int spes_expert_warmup_merge(int32_t n_experts, int32_t dtype, int32_t 
                                       const int64_t* elems, float* sim, int32_t* nbr,
                                       void* scratch, void* stream);
 
+/* spes_expert_warmup_merge for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same computation with the
+ * same arguments, except that the Gram partial sums go to a buffer that is part of the library's
+ * own device image (8 MiB, held by every GPU the library runs on until the process ends) instead
+ * of a caller-provided scratch.  The call allocates and frees nothing.  That buffer covers every
+ * supported problem (n_experts <= 64, at most 512 chunks of the contraction); a problem that
+ * would need more is rejected with SPES_ESHAPE.  All calls on one GPU share the buffer: calls
+ * that overlap in time on one GPU (different streams) race on it; calls on one stream are safe.
+ * Nothing in it needs clearing between calls: every partial a call reads was written by that call.
+ */
+SPES_API int spes_expert_warmup_merge_static(int32_t n_experts, int32_t dtype, int32_t top_K,
+                                             float alpha, const void* w_in, int64_t elems_in,
+                                             int32_t n_mats, const void* const* src,
+                                             void* const* dst, const int64_t* elems, float* sim,
+                                             int32_t* nbr, void* stream);
+
 SPES_API const char* spes_strerror(int code);
 
 #ifdef __cplusplus

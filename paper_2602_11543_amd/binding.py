@@ -67,6 +67,8 @@ def _load() -> ctypes.CDLL:
     lib.spes_warmup_scratch_bytes.argtypes = [i32, i64]
     lib.spes_expert_warmup_merge.restype = i32
     lib.spes_expert_warmup_merge.argtypes = [i32, i32, i32, ctypes.c_float, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.spes_expert_warmup_merge_static.restype = i32
+    lib.spes_expert_warmup_merge_static.argtypes = [i32, i32, i32, ctypes.c_float, vp, i64, i32, vp, vp, vp, vp, vp, vp]
     lib.spes_ref_mfma_rate.restype = i32
     lib.spes_ref_mfma_rate.argtypes = [vp, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.spes_profile_enable.restype = i32
@@ -208,6 +210,18 @@ def spes_expert_warmup_merge(n_experts, dtype, top_K, alpha, w_in, elems_in, src
                                          ctypes.cast(sp, ctypes.c_void_p), ctypes.cast(dp, ctypes.c_void_p),
                                          el.ctypes.data_as(ctypes.c_void_p), _dev(sim), _dev(nbr), _dev(scratch),
                                          _stream(stream)), "spes_expert_warmup_merge")
+
+
+def spes_expert_warmup_merge_static(n_experts, dtype, top_K, alpha, w_in, elems_in, src: Sequence[torch.Tensor],
+                                    dst: Sequence[torch.Tensor], elems: Sequence[int], sim, nbr, stream=None) -> None:
+    n_mats = len(src)
+    sp = (ctypes.c_void_p * max(n_mats, 1))(*[_dev(t).value for t in src])
+    dp = (ctypes.c_void_p * max(n_mats, 1))(*[_dev(t).value for t in dst])
+    el = np.ascontiguousarray(elems, dtype=np.int64)
+    _check(_lib.spes_expert_warmup_merge_static(n_experts, dtype, top_K, ctypes.c_float(alpha), _dev(w_in), elems_in, n_mats,
+                                                ctypes.cast(sp, ctypes.c_void_p), ctypes.cast(dp, ctypes.c_void_p),
+                                                el.ctypes.data_as(ctypes.c_void_p), _dev(sim), _dev(nbr), _stream(stream)),
+           "spes_expert_warmup_merge_static")
 
 
 def spes_profile_enable(on: bool) -> None:

@@ -2,6 +2,7 @@
 // sequences of the forward, backward, synchronisation and warm-up merge.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 
 #include "kernels.h"
 
@@ -488,6 +489,40 @@ SPES_API int spes_expert_warmup_merge(int32_t n_experts, int32_t dtype, int32_t 
   for (int m = 0; m < n_mats; ++m)
     SPES_TRY(launch_warmup_mix(dtype, M, elems[m], top_K, alpha, src[m], dst[m], nbr, s));
   return SPES_OK;
+}
+
+// Scratch of spes_expert_warmup_merge_static: the Gram partials of the largest supported problem.  Every GPU the
+// library runs on holds its own copy for the life of the process.
+constexpr size_t kStaticScratchBytes = (size_t)kMaxGramGroups * kMaxExperts * kMaxExperts * 4;   // 8 MiB
+static __device__ __align__(256) unsigned char g_warmup_scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+
+// device address of g_warmup_scratch on the current device (the array's name is a host-side stand-in, not an address)
+static int static_scratch(void** out) {
+  static std::mutex mu;
+  static void* ptr[kMaxDevices] = {nullptr};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SPES_EHIP;
+  std::lock_guard<std::mutex> lock(mu);
+  if (ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_warmup_scratch)) != hipSuccess || p == nullptr) return SPES_EHIP;
+    ptr[dev] = p;
+  }
+  *out = ptr[dev];
+  return SPES_OK;
+}
+
+SPES_API int spes_expert_warmup_merge_static(int32_t n_experts, int32_t dtype, int32_t top_K, float alpha, const void* w_in,
+                                             int64_t elems_in, int32_t n_mats, const void* const* src, void* const* dst,
+                                             const int64_t* elems, float* sim, int32_t* nbr, void* stream) {
+  if (n_experts <= 0 || elems_in <= 0) return SPES_EINVAL;
+  if (n_experts > kMaxExperts) return SPES_ESHAPE;
+  if (spes_warmup_scratch_bytes(n_experts, elems_in) > kStaticScratchBytes) return SPES_ESHAPE;
+  void* scratch = nullptr;
+  SPES_TRY(static_scratch(&scratch));
+  return spes_expert_warmup_merge(n_experts, dtype, top_K, alpha, w_in, elems_in, n_mats, src, dst, elems, sim, nbr, scratch,
+                                  stream);
 }
 
 SPES_API int spes_ref_mfma_rate(const void* data, int32_t blocks, int32_t iters, float* sink, double* flop, void* stream) {
