@@ -56,8 +56,10 @@ def profiled_traffic(cfg_name: str, stage: str):
     sf = sw = None
     in_table = False
     for line in open(path):
-        if line.startswith("# HBM traffic per dispatch"):
+        if line.startswith("# HBM"):
             in_table = True
+        elif line.startswith("# calibration"):
+            in_table = False
         elif in_table and line.startswith(kernel):
             cols = line.split()
             fetch, write = float(cols[-2]), float(cols[-1])
