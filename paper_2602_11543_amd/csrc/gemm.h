@@ -45,6 +45,8 @@ struct GemmArgs {
   int c_f32;              // C is float whatever the storage type
   int accumulate;
   int Mdim, Ndim;         // extent of m (kGroupedK) and of n
+  int n_base;             // kRaggedM: first column this launch computes (columns n_base .. Ndim-1); 0 unless a launch is split
+  int rowdot_slot0;       // kEpiDSwiglu: first partial slot this launch writes
   // kRaggedM
   const int* tile_expert;
   const int* tile_row0;
