@@ -2,23 +2,29 @@
 //
 // This is the full-precision path (fp32 storage mode needs 1e-5 agreement, which
 // rules out bf16 matrix cores) and the path for small or oddly strided
-// contractions.  64x64 output tile per 256-thread block, 4x4 outputs per thread,
-// K advanced 16 at a time through LDS.
+// contractions.  (16*TR)x64 output tile per 256-thread block, TR x 4 outputs per thread (TR = 4, 2 or 1: the
+// launcher takes shorter tiles when the taller ones would leave most CUs without a block),
+// K advanced 32 at a time through LDS; the next K-tile is requested into registers
+// before the current one is multiplied, so its memory latency hides behind the FMAs
+// (the shapes this path serves put one block on a CU, where nothing else would).
 #include "gemm.h"
 
 namespace spes {
 namespace {
 
-constexpr int BM = 64, BN = 64, BK = 16;
+constexpr int kRowTile = 64;          // row tile of the ragged-row table; a block takes 16*TR of its rows
+constexpr int BN = 64, BK = 32;
 
 template <typename T>
 __device__ __forceinline__ float ld(const void* base, long idx) {
   return Elem<T>::load(reinterpret_cast<const T*>(base) + idx);
 }
 
-template <typename TA, typename TB, int MODE, int EPI>
+template <typename TA, typename TB, int MODE, int EPI, int TR>
 __global__ __launch_bounds__(256) void gemm_simt_kernel(const GemmArgs g) {
   constexpr bool DUAL = (EPI == kEpiSwiglu);
+  constexpr int BM = 16 * TR;
+  constexpr int kPerA = BM * BK / 256, kPerB = BN * BK / 256;   // elements of an operand tile per thread
   __shared__ float As[BK][BM + 4];
   __shared__ float Bs[DUAL ? 2 : 1][BK][BN + 4];
   __shared__ float Red[EPI == kEpiDSwiglu ? BM : 1][17];
@@ -31,11 +37,12 @@ __global__ __launch_bounds__(256) void gemm_simt_kernel(const GemmArgs g) {
   long k_begin, k_end;   // contraction range
   long b_group = 0, c_group = 0;
   if (MODE == kRaggedM) {
-    const int tile = blockIdx.y;
+    const int tile = blockIdx.y / (kRowTile / BM);
     if (tile >= *g.n_tiles) return;
     const int e = g.tile_expert[tile];
-    m0 = g.tile_row0[tile];
+    m0 = g.tile_row0[tile] + (blockIdx.y % (kRowTile / BM)) * BM;
     m_end = min((long)g.offset[e + 1], m0 + BM);
+    if (m0 >= m_end) return;
     k_begin = 0; k_end = g.Kdim;
     b_group = (long)e * g.b_gs;
   } else {
@@ -51,104 +58,125 @@ __global__ __launch_bounds__(256) void gemm_simt_kernel(const GemmArgs g) {
     c_group = (long)grp * g.c_gs;
   }
 
-  float acc[DUAL ? 2 : 1][4][4];
+  float acc[DUAL ? 2 : 1][TR][4];
 #pragma unroll
   for (int p = 0; p < (DUAL ? 2 : 1); ++p)
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < TR; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j) acc[p][i][j] = 0.f;
   // Long contractions are summed in two levels: every kFlush K-tiles the running sums move into `total`, so the
   // rounding error grows with sqrt(kFlush*BK) + sqrt(K / (kFlush*BK)) instead of sqrt(K).
-  constexpr int kFlush = 8;
-  float total[DUAL ? 2 : 1][4][4];
+  constexpr int kFlush = 4;
+  float total[DUAL ? 2 : 1][TR][4];
 #pragma unroll
   for (int p = 0; p < (DUAL ? 2 : 1); ++p)
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < TR; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j) total[p][i][j] = 0.f;
   int since_flush = 0;
 
   const bool a_kfast = (g.a_ks == 1), b_kfast = (g.b_ks == 1);
   const int npass = DUAL ? 1 : g.npairs;
-  for (int pass = 0; pass < npass; ++pass) {
+  const long ktiles = k_end > k_begin ? (k_end - k_begin + BK - 1) / BK : 0;
+  const long ntiles = ktiles * npass;              // K-tiles of all (A,B) pairs, pair after pair
+
+  // position of this thread's element i inside an operand tile, walking the contiguous direction of the operand
+  // (k fast: kPer consecutive k of one row; k slow: kPer consecutive rows of one k)
+  constexpr int TPA = 256 / BM, TPB = 256 / BN;    // threads per row of the tile, k fast
+  const int a_row = a_kfast ? tid / TPA : (tid & 7) * kPerA, a_k = a_kfast ? (tid % TPA) * kPerA : tid >> 3;
+  const int b_row = b_kfast ? tid / TPB : (tid & 7) * kPerB, b_k = b_kfast ? (tid % TPB) * kPerB : tid >> 3;
+
+  float ra[kPerA], rb[DUAL ? 2 : 1][kPerB];
+  // requests K-tile t (of all pairs) into ra / rb; elements outside the tile's rows, columns or contraction range are 0
+  auto fetch = [&](long t) {
+    const int pass = (int)(t / ktiles);
+    const long kk = k_begin + (t - pass * ktiles) * BK;
     const void* Ap = g.A[pass];
-    for (long kk = k_begin; kk < k_end; kk += BK) {
-      // stage A: 64 x 16 elements, 4 per thread, walking the contiguous direction
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        int ml, kl;
-        if (a_kfast) { ml = tid >> 2; kl = (tid & 3) * 4 + i; } else { kl = tid >> 4; ml = (tid & 15) * 4 + i; }
-        const long m = m0 + ml, k = kk + kl;
-        float v = 0.f;
-        if (m < m_end && k < k_end) {
-          if (MODE == kRaggedM) {
-            const long row = g.a_rows ? (long)g.a_rows[m] : m;
-            v = ld<TA>(Ap, row * g.a_ms + k * g.a_ks);
-          } else {
-            const long row = g.a_rows ? (long)g.a_rows[k] : k;
-            v = ld<TA>(Ap, m * g.a_ms + row * g.a_ks);
-          }
+    for (int i = 0; i < kPerA; ++i) {
+      const int ml = a_kfast ? a_row : a_row + i, kl = a_kfast ? a_k + i : a_k;
+      const long m = m0 + ml, k = kk + kl;
+      float v = 0.f;
+      if (m < m_end && k < k_end) {
+        if (MODE == kRaggedM) {
+          const long row = g.a_rows ? (long)g.a_rows[m] : m;
+          v = ld<TA>(Ap, row * g.a_ms + k * g.a_ks);
+        } else {
+          const long row = g.a_rows ? (long)g.a_rows[k] : k;
+          v = ld<TA>(Ap, m * g.a_ms + row * g.a_ks);
         }
-        As[kl][ml] = v;
       }
+      ra[i] = v;
+    }
+#pragma unroll
+    for (int p = 0; p < (DUAL ? 2 : 1); ++p) {
+      const void* Bp = g.B[DUAL ? p : pass];
+#pragma unroll
+      for (int i = 0; i < kPerB; ++i) {
+        const int nl = b_kfast ? b_row : b_row + i, kl = b_kfast ? b_k + i : b_k;
+        const long n = n0 + nl, k = kk + kl;
+        float v = 0.f;
+        if (n < g.Ndim && k < k_end) {
+          const long row = (MODE == kGroupedK && g.b_rows) ? (long)g.b_rows[k] : k;
+          v = ld<TB>(Bp, b_group + n * g.b_ns + row * g.b_ks);
+        }
+        rb[p][i] = v;
+      }
+    }
+  };
+
+  if (ntiles > 0) fetch(0);
+  for (long t = 0; t < ntiles; ++t) {
+#pragma unroll
+    for (int i = 0; i < kPerA; ++i) As[a_kfast ? a_k + i : a_k][a_kfast ? a_row : a_row + i] = ra[i];
+#pragma unroll
+    for (int p = 0; p < (DUAL ? 2 : 1); ++p)
+#pragma unroll
+      for (int i = 0; i < kPerB; ++i) Bs[p][b_kfast ? b_k + i : b_k][b_kfast ? b_row : b_row + i] = rb[p][i];
+    __syncthreads();
+    if (t + 1 < ntiles) fetch(t + 1);              // in flight while this tile is multiplied
+#pragma unroll
+    for (int k = 0; k < BK; ++k) {
+      float a[TR];
+#pragma unroll
+      for (int i = 0; i < TR; ++i) a[i] = As[k][ty * TR + i];
 #pragma unroll
       for (int p = 0; p < (DUAL ? 2 : 1); ++p) {
-        const void* Bp = g.B[DUAL ? p : pass];
+        float b[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          int nl, kl;
-          if (b_kfast) { nl = tid >> 2; kl = (tid & 3) * 4 + i; } else { kl = tid >> 4; nl = (tid & 15) * 4 + i; }
-          const long n = n0 + nl, k = kk + kl;
-          float v = 0.f;
-          if (n < g.Ndim && k < k_end) {
-            const long row = (MODE == kGroupedK && g.b_rows) ? (long)g.b_rows[k] : k;
-            v = ld<TB>(Bp, b_group + n * g.b_ns + row * g.b_ks);
-          }
-          Bs[p][kl][nl] = v;
-        }
+        for (int j = 0; j < 4; ++j) b[j] = Bs[p][k][tx * 4 + j];
+#pragma unroll
+        for (int i = 0; i < TR; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[p][i][j] = fmaf(a[i], b[j], acc[p][i][j]);
       }
-      __syncthreads();
-#pragma unroll
-      for (int k = 0; k < BK; ++k) {
-        float a[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) a[i] = As[k][ty * 4 + i];
-#pragma unroll
-        for (int p = 0; p < (DUAL ? 2 : 1); ++p) {
-          float b[4];
-#pragma unroll
-          for (int j = 0; j < 4; ++j) b[j] = Bs[p][k][tx * 4 + j];
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) acc[p][i][j] = fmaf(a[i], b[j], acc[p][i][j]);
-        }
-      }
-      if (++since_flush == kFlush) {
-        since_flush = 0;
-#pragma unroll
-        for (int p = 0; p < (DUAL ? 2 : 1); ++p)
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) { total[p][i][j] += acc[p][i][j]; acc[p][i][j] = 0.f; }
-      }
-      __syncthreads();
     }
+    if (++since_flush == kFlush) {
+      since_flush = 0;
+#pragma unroll
+      for (int p = 0; p < (DUAL ? 2 : 1); ++p)
+#pragma unroll
+        for (int i = 0; i < TR; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) { total[p][i][j] += acc[p][i][j]; acc[p][i][j] = 0.f; }
+    }
+    __syncthreads();
   }
 #pragma unroll
   for (int p = 0; p < (DUAL ? 2 : 1); ++p)
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < TR; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j) acc[p][i][j] += total[p][i][j];
 
-  float dots[4] = {0.f, 0.f, 0.f, 0.f};
+  float dots[TR];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const long m = m0 + ty * 4 + i;
+  for (int i = 0; i < TR; ++i) dots[i] = 0.f;
+#pragma unroll
+  for (int i = 0; i < TR; ++i) {
+    const long m = m0 + ty * TR + i;
     if (m >= m_end) continue;
     const float rs = (EPI == kEpiDSwiglu) ? g.row_scale[m] : 1.f;
 #pragma unroll
@@ -184,7 +212,7 @@ __global__ __launch_bounds__(256) void gemm_simt_kernel(const GemmArgs g) {
   if (EPI == kEpiDSwiglu) {
     // gate-gradient partial of this column tile: fixed-order sum over the 16 column threads of each row
 #pragma unroll
-    for (int i = 0; i < 4; ++i) Red[ty * 4 + i][tx] = dots[i];
+    for (int i = 0; i < TR; ++i) Red[ty * TR + i][tx] = dots[i];
     __syncthreads();
     if (tid < BM && m0 + tid < m_end) {
       float sum = 0.f;
@@ -195,17 +223,29 @@ __global__ __launch_bounds__(256) void gemm_simt_kernel(const GemmArgs g) {
   }
 }
 
-template <typename TA, typename TB, int MODE, int EPI>
-int launch(const GemmArgs& g, hipStream_t s) {
+template <typename TA, typename TB, int MODE, int EPI, int TR>
+int launch_tile(const GemmArgs& g, hipStream_t s) {
+  constexpr int BM = 16 * TR;
   dim3 grid;
   if (MODE == kRaggedM) {
-    grid = dim3(cdiv(g.Ndim, BN), g.max_tiles, 1);
+    grid = dim3(cdiv(g.Ndim, BN), g.max_tiles * (kRowTile / BM), 1);
   } else {
     grid = dim3(cdiv(g.Ndim, BN), cdiv(g.Mdim, BM), g.n_groups);
   }
   if (grid.x == 0 || grid.y == 0 || grid.z == 0) return SPES_OK;
-  hipLaunchKernelGGL((gemm_simt_kernel<TA, TB, MODE, EPI>), grid, dim3(256), 0, s, g);
+  hipLaunchKernelGGL((gemm_simt_kernel<TA, TB, MODE, EPI, TR>), grid, dim3(256), 0, s, g);
   return hipGetLastError() == hipSuccess ? SPES_OK : SPES_EHIP;
+}
+
+// 64-row tiles when they give every CU two blocks or more, otherwise 32- or 16-row tiles (a block of a small problem
+// is bound by its own serial K loop, so more, shorter blocks finish sooner)
+template <typename TA, typename TB, int MODE, int EPI>
+int launch(const GemmArgs& g, hipStream_t s) {
+  const long rows64 = (MODE == kRaggedM) ? g.max_tiles : (long)cdiv(g.Mdim, kRowTile) * g.n_groups;
+  const long blocks64 = rows64 * cdiv(g.Ndim, BN);
+  if (blocks64 >= 512) return launch_tile<TA, TB, MODE, EPI, 4>(g, s);
+  if (blocks64 >= 256) return launch_tile<TA, TB, MODE, EPI, 2>(g, s);
+  return launch_tile<TA, TB, MODE, EPI, 1>(g, s);
 }
 
 template <typename TA, typename TB>
@@ -222,7 +262,7 @@ int dispatch(int mode, int epi, const GemmArgs& g, hipStream_t s) {
 }  // namespace
 
 // Row tile of the ragged-M table this kernel expects, and its column tile.
-int simt_row_tile() { return BM; }
+int simt_row_tile() { return kRowTile; }
 int simt_col_tile() { return BN; }
 
 int launch_gemm_simt(int dtype_a, int dtype_b, int mode, int epi, const GemmArgs& g, hipStream_t s) {
