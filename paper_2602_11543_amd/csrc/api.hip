@@ -16,7 +16,7 @@ constexpr int kRouterSplit = 64;   // chunks of the token axis in the router wei
 struct Layout {
   spes_moe_ctx_layout pub;
   size_t block_counts, tab_simt, tab_mfma, row_token, row_gate, hcorr, dgate_part, da, db, hg, dxp, wr_part, dlogits_bf, dxr, aux, aux_part;
-  int max_tiles, max_tiles_mfma, max_col_tiles;
+  int max_tiles, max_tiles_mfma, est_tiles_mfma, max_col_tiles;
 };
 
 bool shape_ok(const spes_moe_shape* s) {
@@ -50,6 +50,7 @@ Layout make_layout(const spes_moe_shape* s) {
   const size_t R = T * k, es = s->dtype == SPES_F32 ? 4 : 2;
   L.max_tiles = (int)(R / 64 + M + 1);
   L.max_tiles_mfma = (int)(R / 256 + M + 1);
+  L.est_tiles_mfma = (int)(R / 256 + (M + 1) / 2);   // expected count: half of the experts end in a partly filled tile
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += round_up(bytes, 256); return o; };
   L.pub.logits = take(kLogitSplit * T * M * 4);   // partial score matrices; the first one ends up holding the scores
@@ -103,6 +104,7 @@ void ragged_tables(GemmArgs& g, void* ctx, const Layout& L, int dt) {
   g.tile_row0 = tab + 1 + L.max_tiles;
   g.offset = at<int>(ctx, L.pub.offset);
   g.max_tiles = dt == SPES_BF16 ? L.max_tiles_mfma : L.max_tiles;   // launch bound on the number of row tiles
+  g.est_tiles = dt == SPES_BF16 ? L.est_tiles_mfma : 0;
 }
 
 GemmArgs blank() {
@@ -285,7 +287,7 @@ SPES_API int spes_moe_bwd(const spes_moe_shape* shape, const void* dy, const voi
   // u = dy[token] W_d per routed row; its epilogue yields the gate gradient <u, h> (per column tile) and,
   // through the SwiGLU, da and db of the gate-scaled upstream gradient
   const long R = (long)T * k;
-  const int n_part = dt == SPES_BF16 ? mfma_rowdot_parts(f) : cdiv(f, simt_col_tile());
+  const int n_part = dt == SPES_BF16 ? mfma_rowdot_parts(f, L.est_tiles_mfma) : cdiv(f, simt_col_tile());
   // bf16 storage: the two router contractions run on the matrix cores from a bf16 copy of dlogits
   const bool router_mfma = dt == SPES_BF16 && M % 8 == 0;
   prof_begin(1, s);

@@ -53,6 +53,7 @@ struct GemmArgs {
   const int* n_tiles;
   const int* offset;      // [M+1] first routed row of each expert
   int max_tiles;
+  int est_tiles;          // expected number of row tiles (the count itself is only known on the device); 0: unknown
   unsigned long long c2_skip;  // kEpiDSwiglu: bit e set = nothing reads C[2] for expert e's rows; the matrix-core path leaves them unwritten
   // kGroupedK
   int n_groups;
@@ -68,6 +69,6 @@ int launch_gemm_mfma(int mode, int epi, bool a_kcontig, bool b_kcontig, const Ge
 int simt_row_tile();
 int simt_col_tile();
 int mfma_row_tile();
-int mfma_rowdot_parts(int ndim);
+int mfma_rowdot_parts(int ndim, int est_tiles);
 
 }  // namespace spes

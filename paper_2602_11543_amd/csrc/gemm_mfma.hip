@@ -721,9 +721,21 @@ int launch(const GemmArgs& g, hipStream_t s) {
 
 }  // namespace
 
+// Few tiles: a launch costs its number of rounds of 256 concurrent tiles, the last of them partly empty.  Half-width
+// tiles cost 0.6 of a full one each and fill the rounds better; they are taken where that arithmetic says so (a layer
+// of a few thousand tokens), never for a launch of many rounds.  est_tiles: expected number of row tiles (0: unknown).
+static bool few_tiles_narrow(int ndim, int est_tiles) {
+  if (est_tiles <= 0 || ndim % Tile::BN != 0) return false;
+  const long full = (long)est_tiles * (ndim / Tile::BN);
+  const long rounds_full = (full + 255) / 256, rounds_half = (2 * full + 255) / 256;
+  return rounds_full <= 4 && 0.6 * rounds_half < 0.95 * rounds_full;
+}
+
 int mfma_row_tile() { return Tile::BM; }
-// number of gate-gradient partials per row that the kEpiDSwiglu epilogue writes for ndim columns
-int mfma_rowdot_parts(int ndim) { return 2 * cdiv(ndim, Tile::BN); }
+// number of gate-gradient partials per row that the kEpiDSwiglu epilogue writes for ndim columns (two per column tile)
+int mfma_rowdot_parts(int ndim, int est_tiles) {
+  return few_tiles_narrow(ndim, est_tiles) ? 2 * (ndim / TileNarrow::BN) : 2 * cdiv(ndim, Tile::BN);
+}
 
 // bf16 operands only.  a_kcontig / b_kcontig: the contraction index is the fast memory axis of that operand.
 int launch_gemm_mfma(int mode, int epi, bool a_kcontig, bool b_kcontig, const GemmArgs& g, hipStream_t s) {
@@ -735,6 +747,7 @@ int launch_gemm_mfma(int mode, int epi, bool a_kcontig, bool b_kcontig, const Ge
     if (epi != kEpiSwiglu && g.n_base == 0 && g.Ndim > Tile::BN && tail > 0 && tail <= TileNarrow::BN) {
       GemmArgs head = g, rest = g;
       head.Ndim = g.Ndim - tail;
+      head.est_tiles = 0;            // both parts keep the slot numbering of full-width tiles
       rest.n_base = g.Ndim - tail;
       rest.rowdot_slot0 = 2 * (head.Ndim / Tile::BN);
       const int rc = launch_gemm_mfma(mode, epi, a_kcontig, b_kcontig, head, s);
@@ -742,6 +755,12 @@ int launch_gemm_mfma(int mode, int epi, bool a_kcontig, bool b_kcontig, const Ge
       if (epi == kEpiStore && b_kcontig) return launch<kRaggedM, kEpiStore, true, true, false, false, TileNarrow>(rest, s);
       if (epi == kEpiStore && !b_kcontig) return launch<kRaggedM, kEpiStore, true, false, false, false, TileNarrow>(rest, s);
       if (epi == kEpiDSwiglu && !b_kcontig) return launch<kRaggedM, kEpiDSwiglu, true, false, false, false, TileNarrow>(rest, s);
+      return SPES_EINVAL;
+    }
+    if (epi != kEpiSwiglu && g.n_base == 0 && few_tiles_narrow(g.Ndim, g.est_tiles)) {
+      if (epi == kEpiStore && b_kcontig) return launch<kRaggedM, kEpiStore, true, true, false, false, TileNarrow>(g, s);
+      if (epi == kEpiStore && !b_kcontig) return launch<kRaggedM, kEpiStore, true, false, false, false, TileNarrow>(g, s);
+      if (epi == kEpiDSwiglu && !b_kcontig) return launch<kRaggedM, kEpiDSwiglu, true, false, false, false, TileNarrow>(g, s);
       return SPES_EINVAL;
     }
     if (epi == kEpiSwiglu && b_kcontig) return launch<kRaggedM, kEpiSwiglu, true, true>(g, s);
