@@ -65,6 +65,14 @@ def test_layer_parity(name, device):
     # outputs wide enough for the grouped tile order (at least 12 column tiles), with a ragged last group of row tiles
     dict(T=700, d=64, M=5, f=1600, k=2, n_trainable=2, dtype="bf16"),
     dict(T=700, d=3200, M=5, f=64, k=2, n_trainable=2, dtype="bf16"),
+    # a last column tile that is at most half full runs as a launch of its own on the half-width tile: exactly half
+    # (d and f = 128 beyond a multiple of 256), and a quarter (64 beyond)
+    dict(T=600, d=384, M=6, f=640, k=2, n_trainable=2, dtype="bf16"),
+    dict(T=600, d=320, M=6, f=576, k=2, renorm=1, n_trainable=3, trainable="random", dtype="bf16"),
+    # few tiles and outputs a multiple of 256 wide: whole launches on the half-width tile, the SwiGLU-backward one included
+    dict(T=1024, d=256, M=4, f=512, k=2, n_trainable=2, dtype="bf16"),
+    # fp32 path with enough 64-row tiles for the tallest of its three tile heights (the cases above use the shorter two)
+    dict(T=2048, d=128, M=4, f=512, k=2, n_trainable=2),
 ])
 def test_layer_edge_cases(kw, device):
     kw = dict(kw); kw.setdefault("router_sigma", 0.3)
