@@ -6,7 +6,7 @@
 //  kRaggedM  (forward and input-gradient GEMMs): the rows m are the routed rows
 //            in expert-contiguous order; a device-side tile table maps each row
 //            tile to its expert, whose weight matrix is operand B.
-//  kGroupedK (weight gradients, router GEMMs, Gram matrix): each group
+//  kGroupedK (weight gradients, router GEMMs, the fp32 Gram matrix): each group
 //            contracts over its own range of k -- the routed rows of one
 //            trainable expert, or a uniform chunk of a long contraction.
 #pragma once

@@ -693,7 +693,8 @@ __global__ __launch_bounds__(256, C::MINB) void gemm_mfma_kernel(const GemmArgs 
 // one tile configuration: 256 x 256 x 64, one block per CU (144 KB of LDS, 256 accumulators per lane in AGPRs)
 typedef Cfg<256, 256, 64, 1> Tile;
 
-// narrow outputs (the router's M <= 64 expert columns): half the columns, so half the matrix work on padding
+// narrow outputs (the router's M <= 64 expert columns: half the matrix work on padding), the half-full last column
+// tile of a ragged-row GEMM, and launches of few tiles
 typedef Cfg<256, 128, 64, 1> TileNarrow;
 // few output rows (the router's weight gradient has M <= 64 of them)
 typedef Cfg<128, 256, 64, 1> TileShort;
@@ -770,8 +771,6 @@ int launch_gemm_mfma(int mode, int epi, bool a_kcontig, bool b_kcontig, const Ge
     return SPES_EINVAL;
   }
   if (epi != kEpiStore) return SPES_EINVAL;
-  if (a_kcontig && b_kcontig && g.Mdim <= TileSmall::BM && g.Ndim <= TileSmall::BN)      // the warm-up merge's Gram matrix
-    return launch<kGroupedK, kEpiStore, true, true, false, false, TileSmall>(g, s);
   if (a_kcontig && b_kcontig)
     return g.Ndim <= TileNarrow::BN ? launch<kGroupedK, kEpiStore, true, true, false, false, TileNarrow>(g, s)
                                     : launch<kGroupedK, kEpiStore, true, true>(g, s);
