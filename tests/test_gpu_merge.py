@@ -88,7 +88,10 @@ def _structured_experts(M, E, dtype, seed):
 
 
 @pytest.mark.parametrize("dtype,M,E,K,alpha", [("f32", 8, 4096, 4, 0.1), ("bf16", 64, 8200, 4, 0.1), ("bf16", 16, 3000 * 8, 3, 1.0),
-                                               ("f32", 6, 512, 5, 1.0), ("f32", 8, 1024, 4, 0.0)])
+                                               ("f32", 6, 512, 5, 1.0), ("f32", 8, 1024, 4, 0.0),
+                                               # several column runs per XCD with a ragged last run, K not a multiple of
+                                               # the four peers requested at a time; K = M - 1 with whole XCD turns empty
+                                               ("bf16", 24, 8 * (2048 * 8 + 5), 7, 0.3), ("f32", 12, 8 * (128 * 9 + 1), 11, 0.5)])
 def test_warmup_merge_parity(dtype, M, E, K, alpha, device):
     print(f"[case] warmup {dtype} M={M} E={E} K={K} alpha={alpha}", flush=True)
     dt = S.SPES_F32 if dtype == "f32" else S.SPES_BF16
